@@ -1,0 +1,238 @@
+/*
+ * CPU oracle for value-driven memory retrieval (Sec. 3.2 of the paper) -- TEST INFRASTRUCTURE.
+ *
+ * Plain, slow, fp64, by-the-definition code.  It exists only so that tests, the smoke check and
+ * the benchmark's CPU-baseline leg can compare the GPU library against it.  It shares no code,
+ * header, table or helper with the GPU library, and nothing in the product path may call it.
+ *
+ * What it computes, in the paper's order (Sec. 3.2):
+ *   1. dense recall: cosine similarity of a query against every stored entry, keep the K best
+ *      (the "top-K candidate pool");
+ *   2. value filter: re-rank the pool with the stage's Q values and keep the final N items;
+ *   3. the unified Monte-Carlo value update Q <- Q + alpha (r - Q) for every id handed in
+ *      (Eq. "unified update" of Sec. 3.2; App. A, bandit-style update).
+ *
+ * Readings where the paper gives no formula (each is pinned by a test on invariants):
+ *   - similarity is the cosine of the *stored* (rounded to the bank's element type) vectors,
+ *     queries being rounded to the same type first;
+ *   - ties are broken towards the lower id, in both selections;
+ *   - the re-rank score is (1-lam)*z(sim) + lam*z(Q), z being the z-score over the query's own
+ *     candidate pool with population standard deviation and denominator (std + 1e-6);
+ *   - duplicate ids in one update batch are applied one after another in array order, which is
+ *     what the unrolled recursion in the proof of the constant-step-size lemma (App. A) describes.
+ *
+ * Pins: tests/test_oracle_pins.py (brute force, closed forms, invariants, library cross-checks).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { ORC_F32 = 0, ORC_BF16 = 1, ORC_F16 = 2 };
+
+/* ---------- element rounding: fp32 -> bank element type -> fp32, round-to-nearest-even ---------- */
+
+static float bits_to_float(uint32_t u) { float f; memcpy(&f, &u, 4); return f; }
+static uint32_t float_to_bits(float f) { uint32_t u; memcpy(&u, &f, 4); return u; }
+
+/* bfloat16 keeps the top 16 bits of the fp32 pattern; RNE on the dropped 16 bits. */
+static float round_bf16(float x) {
+    uint32_t u = float_to_bits(x);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return bits_to_float((u | 0x00400000u) & 0xffff0000u); /* NaN */
+    uint32_t dropped = u & 0xffffu, keep = u >> 16;
+    if (dropped > 0x8000u || (dropped == 0x8000u && (keep & 1u))) keep += 1; /* may carry into inf: correct */
+    return bits_to_float(keep << 16);
+}
+
+/* IEEE binary16: 5 exponent bits (bias 15), 10 fraction bits, gradual underflow.  Done in exact
+ * arithmetic: scale so that one unit in the last place of the target is 1.0, round to an integer
+ * with ties-to-even, scale back. */
+static float round_f16(float x) {
+    if (isnan(x) || isinf(x) || x == 0.0f) return x;
+    double a = fabs((double)x);
+    int e;
+    (void)frexp(a, &e);            /* a = m * 2^e, m in [0.5,1) -> exponent of leading bit is e-1 */
+    int lead = e - 1;
+    if (lead < -14) lead = -14;    /* subnormal range shares the ulp of the smallest normal */
+    double ulp = ldexp(1.0, lead - 10);
+    double q = a / ulp;            /* exact: power-of-two scaling */
+    double fl = floor(q), frac = q - fl;
+    if (frac > 0.5 || (frac == 0.5 && fmod(fl, 2.0) == 1.0)) fl += 1.0;
+    double r = fl * ulp;
+    if (r >= 65520.0) r = INFINITY; /* 65504 is the largest finite value; halfway point rounds up */
+    return (float)(x < 0 ? -r : r);
+}
+
+/* out[i] = value the bank would hold for in[i], widened back to fp32 (exact). */
+int orc_round_to_store(const float* in, int64_t count, int dtype, float* out) {
+    if (dtype != ORC_F32 && dtype != ORC_BF16 && dtype != ORC_F16) return 1;
+    for (int64_t i = 0; i < count; ++i)
+        out[i] = dtype == ORC_F32 ? in[i] : dtype == ORC_BF16 ? round_bf16(in[i]) : round_f16(in[i]);
+    return 0;
+}
+
+/* ---------- step 1: dense recall ---------- */
+
+typedef struct { double sim; int32_t id; } pair_t;
+
+/* sim descending, then id ascending */
+static int pair_cmp(const void* pa, const void* pb) {
+    const pair_t* a = (const pair_t*)pa; const pair_t* b = (const pair_t*)pb;
+    if (a->sim > b->sim) return -1;
+    if (a->sim < b->sim) return 1;
+    return (a->id > b->id) - (a->id < b->id);
+}
+
+static double inv_norm(const float* v, int d) {
+    double ss = 0.0;
+    for (int i = 0; i < d; ++i) ss += (double)v[i] * (double)v[i];
+    return 1.0 / sqrt(ss);
+}
+
+/*
+ * store   [N][d]  stored (already rounded, widened) bank rows, ids id_base .. id_base+N-1
+ * queries [B][d]  stored-type-rounded queries
+ * out_ids/out_sims [B][k1]: the min(k1,N) best by (sim desc, id asc); unused slots: id -1, sim -inf.
+ * Every similarity is computed and all N pairs are fully sorted.  threads<=1: serial.
+ */
+int orc_recall(const float* store, int64_t N, int d, int32_t id_base,
+               const float* queries, int B, int k1,
+               int32_t* out_ids, double* out_sims, int threads) {
+    if (N < 0 || d <= 0 || B < 0 || k1 < 1) return 1;
+    double* invn = (double*)malloc(sizeof(double) * (size_t)(N > 0 ? N : 1));
+    if (!invn) return 2;
+    for (int64_t n = 0; n < N; ++n) invn[n] = inv_norm(store + n * d, d);
+    int failed = 0;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(dynamic, 1) num_threads(threads > 1 ? threads : 1)
+#endif
+    for (int b = 0; b < B; ++b) {
+        pair_t* all = (pair_t*)malloc(sizeof(pair_t) * (size_t)(N > 0 ? N : 1));
+        if (!all) { failed = 1; continue; }
+        const float* q = queries + (int64_t)b * d;
+        double invq = inv_norm(q, d);
+        for (int64_t n = 0; n < N; ++n) {
+            const float* e = store + n * d;
+            double dot = 0.0;
+            for (int i = 0; i < d; ++i) dot += (double)q[i] * (double)e[i];
+            all[n].sim = dot * invq * invn[n];
+            all[n].id = id_base + (int32_t)n;
+        }
+        qsort(all, (size_t)N, sizeof(pair_t), pair_cmp);
+        for (int j = 0; j < k1; ++j) {
+            if (j < N) { out_ids[(int64_t)b * k1 + j] = all[j].id; out_sims[(int64_t)b * k1 + j] = all[j].sim; }
+            else       { out_ids[(int64_t)b * k1 + j] = -1;        out_sims[(int64_t)b * k1 + j] = -INFINITY; }
+        }
+        free(all);
+    }
+    free(invn);
+    return failed ? 2 : 0;
+}
+
+/* Similarities of one query against a given list of ids (used to judge near-ties and to re-rank a
+ * candidate set chosen by someone else). */
+int orc_sims_of(const float* store, int64_t N, int d, const float* query,
+                const int32_t* ids, int count, double* out_sims) {
+    double invq = inv_norm(query, d);
+    for (int j = 0; j < count; ++j) {
+        if (ids[j] < 0 || ids[j] >= N) { out_sims[j] = -INFINITY; continue; }
+        const float* e = store + (int64_t)ids[j] * d;
+        double dot = 0.0;
+        for (int i = 0; i < d; ++i) dot += (double)query[i] * (double)e[i];
+        out_sims[j] = dot * invq * inv_norm(e, d);
+    }
+    return 0;
+}
+
+/* ---------- step 2: value filter (re-rank the pool, keep the final items) ---------- */
+
+static void zscores(const double* x, int k, double* z) {
+    double mean = 0.0;
+    for (int i = 0; i < k; ++i) mean += x[i];
+    mean /= (double)k;
+    double var = 0.0;
+    for (int i = 0; i < k; ++i) var += (x[i] - mean) * (x[i] - mean);
+    var /= (double)k;                       /* population variance, as the paper's own running sigma */
+    double denom = sqrt(var) + 1e-6;
+    for (int i = 0; i < k; ++i) z[i] = (x[i] - mean) / denom;
+}
+
+/*
+ * One query.  cand_ids/cand_sims: the pool (count entries, ids >= 0).  qtable: the stage's Q values
+ * indexed by id.  Writes min(k2,count) results sorted by (score desc, id asc); pads with -1 / -inf.
+ * out_scores_f32 may be NULL; out_scores_f64 may be NULL.
+ */
+int orc_rerank(const int32_t* cand_ids, const double* cand_sims, int count,
+               const float* qtable, double lam, int k2,
+               int32_t* out_ids, float* out_scores_f32, double* out_scores_f64) {
+    if (count < 0 || k2 < 1) return 1;
+    double* qv = (double*)malloc(sizeof(double) * (size_t)(count + 1));
+    double* zs = (double*)malloc(sizeof(double) * (size_t)(count + 1));
+    double* zq = (double*)malloc(sizeof(double) * (size_t)(count + 1));
+    pair_t* sc = (pair_t*)malloc(sizeof(pair_t) * (size_t)(count + 1));
+    if (count > 0) {
+        for (int i = 0; i < count; ++i) qv[i] = (double)qtable[cand_ids[i]];
+        zscores(cand_sims, count, zs);
+        zscores(qv, count, zq);
+        for (int i = 0; i < count; ++i) {
+            sc[i].sim = (1.0 - lam) * zs[i] + lam * zq[i];
+            sc[i].id = cand_ids[i];
+        }
+        qsort(sc, (size_t)count, sizeof(pair_t), pair_cmp);
+    }
+    for (int j = 0; j < k2; ++j) {
+        int ok = j < count;
+        out_ids[j] = ok ? sc[j].id : -1;
+        if (out_scores_f32) out_scores_f32[j] = ok ? (float)sc[j].sim : -INFINITY;
+        if (out_scores_f64) out_scores_f64[j] = ok ? sc[j].sim : -INFINITY;
+    }
+    free(qv); free(zs); free(zq); free(sc);
+    return 0;
+}
+
+/* ---------- step 3: unified value update ---------- */
+
+/* Reference: fp64 state seeded from the fp32 table, rounded back to fp32 once at the end.
+ * Ids outside [0,N) are skipped; returns how many were skipped. */
+int64_t orc_update_q64(float* qtable, int64_t N, const int32_t* ids, const float* rewards,
+                       int64_t M, double alpha) {
+    double* state = (double*)malloc(sizeof(double) * (size_t)(N > 0 ? N : 1));
+    unsigned char* touched = (unsigned char*)calloc((size_t)(N > 0 ? N : 1), 1);
+    int64_t skipped = 0;
+    for (int64_t n = 0; n < N; ++n) state[n] = (double)qtable[n];
+    for (int64_t j = 0; j < M; ++j) {
+        int32_t id = ids[j];
+        if (id < 0 || id >= N) { ++skipped; continue; }
+        state[id] = state[id] + alpha * ((double)rewards[j] - state[id]);
+        touched[id] = 1;
+    }
+    for (int64_t n = 0; n < N; ++n) if (touched[n]) qtable[n] = (float)state[n];
+    free(state); free(touched);
+    return skipped;
+}
+
+/* Same recurrence carried in fp32, one rounding per operation, no fused multiply-add: the value a
+ * sequential single-precision implementation reaches bit for bit. */
+int64_t orc_update_q32(float* qtable, int64_t N, const int32_t* ids, const float* rewards,
+                       int64_t M, float alpha) {
+    int64_t skipped = 0;
+    for (int64_t j = 0; j < M; ++j) {
+        int32_t id = ids[j];
+        if (id < 0 || id >= N) { ++skipped; continue; }
+        volatile float diff = rewards[j] - qtable[id];
+        volatile float step = alpha * diff;
+        qtable[id] = qtable[id] + step;
+    }
+    return skipped;
+}
+
+int orc_max_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

@@ -1,0 +1,342 @@
+"""Pins for the CPU oracle: every function is checked against something other than itself --
+hand calculations (tests/golden), brute force written out in Python, closed forms from App. A of
+the paper, invariants, and library routines (NumPy fp64 matmul + sort, NumPy/PyTorch rounding)."""
+import json
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+F32, BF16, F16 = 0, 1, 2
+
+
+def _unit(rng, n, d):
+    x = rng.standard_normal((n, d)).astype(np.float32)
+    return (x / np.linalg.norm(x, axis=1, keepdims=True)).astype(np.float32)
+
+
+# ----------------------------------------------------------------------------- rounding
+
+def test_round_bf16_matches_torch_and_ties(orc):
+    rng = np.random.default_rng(1)
+    x = np.concatenate([rng.standard_normal(20000).astype(np.float32) * s for s in (1e-30, 1e-3, 1, 1e5, 1e30)])
+    x = np.concatenate([x, np.array([0.0, -0.0, np.inf, -np.inf, 3.3895e38, 1e-45], np.float32)])
+    got = orc.round_to_store(x, BF16)
+    want = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+    # hand-made halfway cases: bf16 has 8 significant bits, so 1+2^-8 is a tie
+    ties = np.array([1 + 2.0**-8, 1 + 3 * 2.0**-8, 1 + 2.0**-8 + 2.0**-20, 1 + 2.0**-8 - 2.0**-20], np.float32)
+    exp = np.array([1.0, 1 + 2.0**-6, 1 + 2.0**-7, 1.0], np.float32)
+    assert np.array_equal(orc.round_to_store(ties, BF16), exp)
+
+
+def test_round_f16_matches_numpy_and_ties(orc):
+    rng = np.random.default_rng(2)
+    x = np.concatenate([rng.standard_normal(20000).astype(np.float32) * s
+                        for s in (1e-9, 6e-8, 1e-5, 1e-3, 1, 300, 7e4)])
+    x = np.concatenate([x, np.array([0.0, -0.0, np.inf, -np.inf, 65504, 65519.99, 65520, 2.0**-24,
+                                     2.0**-25, 2.0**-25 * 1.0001, 3 * 2.0**-25], np.float32)])
+    got = orc.round_to_store(x, F16)
+    with np.errstate(over="ignore"):
+        want = x.astype(np.float16).astype(np.float32)
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+    ties = np.array([1 + 2.0**-11, 1 + 3 * 2.0**-11, 2048 + 1, 2048 + 3], np.float32)
+    exp = np.array([1.0, 1 + 2.0**-9, 2048, 2052], np.float32)
+    assert np.array_equal(orc.round_to_store(ties, F16), exp)
+
+
+def test_round_f32_is_identity(orc):
+    x = np.random.default_rng(3).standard_normal(1000).astype(np.float32)
+    assert np.array_equal(orc.round_to_store(x, F32), x)
+
+
+# ----------------------------------------------------------------------------- recall
+
+def _brute_recall(store, q, k1):
+    """Definition written out with Python floats (fp64): cosine against every row, full sort."""
+    out = []
+    for b in range(q.shape[0]):
+        nq = math.sqrt(sum(float(v) * float(v) for v in q[b]))
+        pairs = []
+        for n in range(store.shape[0]):
+            ne = math.sqrt(sum(float(v) * float(v) for v in store[n]))
+            dot = sum(float(a) * float(c) for a, c in zip(q[b], store[n]))
+            pairs.append((-(dot / (nq * ne)), n))
+        pairs.sort()
+        out.append(pairs[:k1])
+    return out
+
+
+def test_recall_brute_force_tiny_with_ties(orc):
+    rng = np.random.default_rng(4)
+    store = rng.integers(-3, 4, size=(48, 6)).astype(np.float32)
+    store[np.abs(store).sum(1) == 0, 0] = 1
+    store[17] = store[5]          # exact duplicates: identical sims, lower id must come first
+    store[40] = store[5]
+    store[9] = store[33]
+    q = np.stack([store[5], store[33] * 2.5, rng.integers(-3, 4, 6).astype(np.float32) + 0.5])
+    ids, sims = orc.recall(store, q, 12)
+    brute = _brute_recall(store, q, 12)
+    for b in range(3):
+        assert [p[1] for p in brute[b]] == ids[b].tolist()
+        assert np.allclose([-p[0] for p in brute[b]], sims[b], rtol=0, atol=1e-14)
+    assert ids[0, :3].tolist() == [5, 17, 40] and abs(sims[0, 0] - 1.0) < 1e-14
+    assert ids[1, :2].tolist() == [9, 33]
+
+
+def test_recall_one_hot_bank_and_self_query(orc):
+    d = 16
+    store = np.eye(d, dtype=np.float32) * np.arange(1, d + 1, dtype=np.float32)[:, None]   # scaled one-hots
+    q = np.zeros((2, d), np.float32)
+    q[0, 3] = 5.0
+    q[1, 7], q[1, 2] = 3.0, 4.0
+    ids, sims = orc.recall(store, q, d)
+    assert ids[0, 0] == 3 and sims[0, 0] == 1.0 and np.all(sims[0, 1:] == 0.0)
+    assert ids[0, 1:].tolist() == [i for i in range(d) if i != 3]        # all tied at 0: id ascending
+    assert ids[1, :2].tolist() == [2, 7] and np.allclose(sims[1, :2], [0.8, 0.6], atol=1e-15)
+
+
+def test_recall_matches_numpy_gemm_and_sort(orc):
+    rng = np.random.default_rng(5)
+    store = rng.standard_normal((3000, 96)).astype(np.float32) * rng.uniform(0.1, 10, (3000, 1)).astype(np.float32)
+    q = rng.standard_normal((7, 96)).astype(np.float32)
+    ids, sims = orc.recall(store, q, 50, threads=2)
+    S = (q.astype(np.float64) @ store.astype(np.float64).T)
+    S /= np.linalg.norm(q.astype(np.float64), axis=1)[:, None]
+    S /= np.linalg.norm(store.astype(np.float64), axis=1)[None, :]
+    for b in range(7):
+        order = np.lexsort((np.arange(3000), -S[b]))[:50]
+        assert np.array_equal(order, ids[b])
+        assert np.allclose(S[b][order], sims[b], rtol=0, atol=1e-13)
+
+
+def test_recall_scale_and_permutation_invariance(orc):
+    rng = np.random.default_rng(6)
+    store = rng.standard_normal((500, 32)).astype(np.float32)
+    q = rng.standard_normal((4, 32)).astype(np.float32)
+    ids, sims = orc.recall(store, q, 20)
+    # power-of-two scalings are exact in floating point: sims must not move at all beyond 1 ulp
+    ids2, sims2 = orc.recall(store * np.float32(4.0), q * np.float32(0.125), 20)
+    assert np.array_equal(ids, ids2) and np.allclose(sims, sims2, rtol=0, atol=1e-15)
+    perm = rng.permutation(500)
+    ids3, sims3 = orc.recall(store[perm], q, 20)
+    assert np.array_equal(perm[ids3], ids) and np.allclose(sims3, sims, rtol=0, atol=1e-15)
+
+
+def test_recall_padding_and_chunk_merge(orc):
+    rng = np.random.default_rng(7)
+    store = rng.standard_normal((10, 8)).astype(np.float32)
+    q = rng.standard_normal((2, 8)).astype(np.float32)
+    ids, sims = orc.recall(store, q, 16)
+    assert np.all(ids[:, 10:] == -1) and np.all(np.isneginf(sims[:, 10:])) and np.all(ids[:, :10] >= 0)
+    big = rng.standard_normal((300, 8)).astype(np.float32)
+    whole = orc.recall(big, q, 16)
+    parts = [orc.recall(big[a:a + 100], q, 16, id_base=a) for a in (0, 100, 200)]
+    merged = orc.merge_recall(parts, 16)
+    assert np.array_equal(whole[0], merged[0]) and np.array_equal(whole[1], merged[1])
+
+
+def test_recall_uses_stored_representation(orc):
+    """The cosine is taken between the rounded vectors: rounding first, then an fp64 library GEMM."""
+    rng = np.random.default_rng(8)
+    raw = _unit(rng, 400, 64)
+    q = _unit(rng, 3, 64)
+    for dt, tdt in ((BF16, torch.bfloat16), (F16, torch.float16)):
+        st = torch.from_numpy(raw).to(tdt).to(torch.float64).numpy()
+        qq = torch.from_numpy(q).to(tdt).to(torch.float64).numpy()
+        S = (qq @ st.T) / np.linalg.norm(qq, axis=1)[:, None] / np.linalg.norm(st, axis=1)[None, :]
+        ids, sims = orc.recall(orc.round_to_store(raw, dt), orc.round_to_store(q, dt), 10)
+        for b in range(3):
+            order = np.lexsort((np.arange(400), -S[b]))[:10]
+            assert np.array_equal(order, ids[b]) and np.allclose(S[b][order], sims[b], atol=1e-13, rtol=0)
+
+
+# ----------------------------------------------------------------------------- value filter
+
+def test_rerank_hand_example(orc):
+    g = json.load(open(os.path.join(GOLD, "rerank_hand.json")))
+    qt = np.zeros(32, np.float32)
+    for k, v in g["q_of_id"].items():
+        qt[int(k)] = v
+    ids, s32, s64 = orc.rerank(g["cand_ids"], g["cand_sims"], qt, g["lam"], 4)
+    assert ids.tolist() == g["expected_order"]
+    assert np.allclose(s64, g["expected_scores"], rtol=0, atol=g["tolerance"])
+    assert np.array_equal(s32, s64.astype(np.float32))
+
+
+def _brute_rerank(ids, sims, qt, lam, k2):
+    k = len(ids)
+    qs = [float(qt[i]) for i in ids]
+
+    def z(v):
+        m = sum(v) / k
+        sd = math.sqrt(sum((a - m) ** 2 for a in v) / k)
+        return [(a - m) / (sd + 1e-6) for a in v]
+    zs, zq = z([float(s) for s in sims]), z(qs)
+    sc = sorted((-((1 - lam) * a + lam * b), i) for a, b, i in zip(zs, zq, ids))
+    return [i for _, i in sc[:k2]], [-s for s, _ in sc[:k2]]
+
+
+def test_rerank_brute_force(orc):
+    rng = np.random.default_rng(9)
+    qt = rng.uniform(-1, 1, 200).astype(np.float32)
+    for lam in (0.0, 0.25, 0.5, 1.0):
+        ids = rng.choice(200, 24, replace=False).astype(np.int32)
+        sims = np.sort(rng.uniform(0.2, 0.9, 24))[::-1].copy()
+        got_i, _, got_s = orc.rerank(ids, sims, qt, lam, 6)
+        bi, bs = _brute_rerank(ids.tolist(), sims.tolist(), qt, lam, 6)
+        assert got_i.tolist() == bi and np.allclose(got_s, bs, rtol=0, atol=1e-12)
+
+
+def test_rerank_lambda0_is_similarity_ranking_lambda1_is_q_ranking(orc):
+    rng = np.random.default_rng(10)
+    qt = rng.uniform(-1, 1, 500).astype(np.float32)
+    qt[[3, 77, 130]] = 0.75                                    # tied Q values: lower id first at lam=1
+    ids = np.array(sorted(rng.choice(500, 40, replace=False).tolist() + [3, 77, 130]), np.int32)
+    ids = np.unique(ids)
+    rng.shuffle(ids)
+    sims = np.sort(rng.uniform(0, 1, ids.size))[::-1].copy()
+    i0, _, s0 = orc.rerank(ids, sims, qt, 0.0, 8)
+    assert np.array_equal(i0, ids[:8])                          # pure similarity ranking (heuristic baseline)
+    assert np.all(np.diff(s0) <= 0)
+    i1, _, s1 = orc.rerank(ids, sims, qt, 1.0, ids.size)
+    want = sorted(ids.tolist(), key=lambda i: (-float(qt[i]), i))
+    assert i1.tolist() == want                                  # monotone in Q, ties to lower id
+    qv = qt[i1].astype(np.float64)
+    assert np.all(np.diff(s1) <= 1e-15) and np.all((np.diff(qv) < 0) | (np.diff(s1) == 0))
+
+
+def test_rerank_zscore_identities_affine_invariance_and_sets(orc):
+    rng = np.random.default_rng(11)
+    qt = rng.uniform(-1, 1, 300).astype(np.float64)
+    ids = rng.choice(300, 32, replace=False).astype(np.int32)
+    sims = np.sort(rng.uniform(0.5, 0.6, 32))[::-1].copy()
+    _, _, s = orc.rerank(ids, sims, qt.astype(np.float32), 0.0, 32)     # scores == z(sim), sorted
+    sd = sims.std()                                                       # numpy default: population
+    assert abs(s.sum()) < 1e-9 and abs(s.var() - (sd / (sd + 1e-6)) ** 2) < 1e-9
+    assert abs(s[0] - (sims[0] - sims.mean()) / (sd + 1e-6)) < 1e-9
+    # Q -> aQ + b with a > 0 (power-of-two a, small-integer-over-power-of-two b keep fp32 exact)
+    qa = (qt.astype(np.float32) * np.float32(0.5) + np.float32(0.25)).astype(np.float32)
+    i1, _, s1 = orc.rerank(ids, sims, qt.astype(np.float32), 0.5, 8)
+    i2, _, s2 = orc.rerank(ids, sims, qa, 0.5, 8)
+    assert np.array_equal(i1, i2) and np.allclose(s1, s2, rtol=0, atol=2e-6)
+    # k2 == k1 returns the whole pool
+    i3, _, _ = orc.rerank(ids, sims, qt.astype(np.float32), 0.7, 32)
+    assert sorted(i3.tolist()) == sorted(ids.tolist())
+    # constant Q: ranking is the similarity ranking for any lam < 1, z(Q) == 0
+    i4, _, s4 = orc.rerank(ids, sims, np.full(300, 0.3, np.float32), 0.9, 8)
+    assert np.array_equal(i4, ids[:8]) and np.allclose(s4, 0.1 * s[:8], atol=1e-9)
+    # a pool of one: z == 0
+    i5, s5, _ = orc.rerank(ids[:1], sims[:1], qt.astype(np.float32), 0.5, 2)
+    assert i5.tolist() == [ids[0], -1] and s5[0] == 0.0 and np.isneginf(s5[1])
+
+
+# ----------------------------------------------------------------------------- value update
+
+def test_update_hand_example(orc):
+    g = json.load(open(os.path.join(GOLD, "q_update_hand.json")))
+    for t in range(1, len(g["rewards"]) + 1):
+        for fn in (orc.update_q64, orc.update_q32):
+            q, sk = fn(np.array([9.0, g["q0"], 9.0], np.float32), [1] * t, g["rewards"][:t], g["alpha"])
+            assert sk == 0 and q.tolist() == [9.0, g["trajectory"][t - 1], 9.0]
+
+
+def test_update_closed_form_and_constant_reward(orc):
+    """Unrolled recursion from the proof of the constant-step-size lemma (App. A)."""
+    rng = np.random.default_rng(12)
+    alpha, t = 0.1, 37
+    q0 = np.float32(0.4)
+    R = rng.uniform(-1, 1, t).astype(np.float32)
+    ids = np.full(t, 5, np.int32)
+    table = np.zeros(9, np.float32)
+    table[5] = q0
+    closed = (1 - alpha) ** t * float(q0) + alpha * sum((1 - alpha) ** (t - 1 - k) * float(R[k]) for k in range(t))
+    q64, _ = orc.update_q64(table, ids, R, alpha)
+    q32, _ = orc.update_q32(table, ids, R, alpha)
+    assert abs(float(q64[5]) - closed) < 1e-7 and abs(float(q32[5]) - closed) < 2e-6
+    # a reversed reward order must give a different value (the order of duplicates matters)
+    q64r, _ = orc.update_q64(table, ids, R[::-1].copy(), alpha)
+    assert abs(float(q64r[5]) - closed) > 1e-3
+    const = np.full(t, 0.75, np.float32)
+    qc, _ = orc.update_q64(table, ids, const, alpha)
+    assert abs(float(qc[5]) - (0.75 + (1 - alpha) ** t * (float(q0) - 0.75))) < 1e-7
+
+
+def test_update_alpha_one_keeps_last_reward_and_skips_bad_ids(orc):
+    table = np.linspace(-1, 1, 16).astype(np.float32)
+    ids = np.array([3, 7, 3, -1, 3, 16, 7, 100], np.int32)
+    r = np.array([0.1, 0.2, 0.3, 0.4, 0.5, 0.6, 0.7, 0.8], np.float32)
+    for fn in (orc.update_q64, orc.update_q32):
+        q, skipped = fn(table, ids, r, 1.0)
+        assert skipped == 3 and q[3] == np.float32(0.5) and q[7] == np.float32(0.7)
+        mask = np.ones(16, bool)
+        mask[[3, 7]] = False
+        assert np.array_equal(q[mask].view(np.uint32), table[mask].view(np.uint32))   # others bit-unchanged
+
+
+def test_update_bounded_and_order_free_for_distinct_ids(orc):
+    rng = np.random.default_rng(13)
+    table = rng.uniform(-1, 1, 1000).astype(np.float32)
+    ids = rng.integers(0, 1000, 20000).astype(np.int32)
+    r = rng.uniform(-1, 1, 20000).astype(np.float32)
+    for fn in (orc.update_q64, orc.update_q32):
+        q, _ = fn(table, ids, r, 0.3)
+        assert np.all(np.abs(q) <= 1.0)             # boundedness lemma (App. A): convex combinations
+    d_ids = rng.permutation(1000)[:400].astype(np.int32)
+    d_r = rng.uniform(-1, 1, 400).astype(np.float32)
+    p = rng.permutation(400)
+    a, _ = orc.update_q32(table, d_ids, d_r, 0.2)
+    b, _ = orc.update_q32(table, d_ids[p], d_r[p], 0.2)
+    assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+    q32, _ = orc.update_q32(table, ids, r, 0.3)
+    q64, _ = orc.update_q64(table, ids, r, 0.3)
+    assert np.max(np.abs(q32.astype(np.float64) - q64)) < 2e-6
+
+
+def test_update_ema_statistics(orc):
+    """E[Q_t] = mu (1-(1-a)^t) from Q_0=0 and Var -> a/(2-a) sigma_R^2 (constant-step lemma, App. A)."""
+    rng = np.random.default_rng(14)
+    n, alpha, p = 40000, 0.1, 0.3
+    table = np.zeros(n, np.float32)
+    ids = np.arange(n, dtype=np.int32)
+    for t in range(1, 61):
+        table, _ = orc.update_q64(table, ids, (rng.random(n) < p).astype(np.float32), alpha)
+        if t in (5, 20):
+            assert abs(table.mean() - p * (1 - (1 - alpha) ** t)) < 4e-3
+    assert abs(table.mean() - p) < 4e-3
+    assert abs(table.var() - alpha / (2 - alpha) * p * (1 - p)) < 6e-4
+
+
+def test_error_clipped_variant_is_not_what_the_oracle_computes(orc):
+    """Negative control from App. A's remark: clipping the error alone lets iterates grow without
+    bound; the unclipped convex-combination form stays at the reward."""
+    table = np.zeros(2, np.float32)
+    q, _ = orc.update_q64(table, np.zeros(500, np.int32), np.full(500, 100.0, np.float32), 0.5)
+    assert abs(q[0] - 100.0) < 1e-3
+    clipped = 0.0
+    for _ in range(500):
+        clipped += 0.5 * max(-1.0, min(1.0, 100.0 - clipped))
+    assert clipped > 99.0 and abs(clipped - q[0]) < 1.0     # same limit, different path ...
+    early_c, early_q = 0.0, orc.update_q64(table, np.zeros(3, np.int32), np.full(3, 100.0, np.float32), 0.5)[0][0]
+    for _ in range(3):
+        early_c += 0.5 * max(-1.0, min(1.0, 100.0 - early_c))
+    assert abs(early_q - 87.5) < 1e-4 and early_c == 1.5    # ... the oracle follows the unclipped rule
+
+
+# ----------------------------------------------------------------------------- whole retrieval
+
+def test_retrieve_end_to_end_matches_python_definition(orc):
+    rng = np.random.default_rng(15)
+    store = _unit(rng, 64, 8)
+    q = _unit(rng, 3, 8)
+    qt = rng.uniform(-1, 1, 64).astype(np.float32)
+    out = orc.retrieve(store, q, qt, 16, 4, 0.5)
+    brute = _brute_recall(store, q, 16)
+    for b in range(3):
+        ids = [p[1] for p in brute[b]]
+        sims = [-p[0] for p in brute[b]]
+        bi, bs = _brute_rerank(ids, sims, qt, 0.5, 4)
+        assert out["ids"][b].tolist() == bi and np.allclose(out["scores64"][b], bs, atol=1e-9, rtol=0)
