@@ -1,0 +1,152 @@
+"""Benchmark: value-driven memory retrieval on one MI355X.
+
+One step = one pass of the whole hot path over one batch: append B new entries (memory growth,
+Sec. 3.1), retrieve for B queries (dense recall + value filter, Sec. 3.2), update the Q values of the
+B*k2 returned ids (unified value update, Sec. 3.2).  Workload: the clustered bank, N = 1,048,576
+entries, d = 1024, bf16 storage, B = 256, k1 = 128, k2 = 16, lambda = 0.5, synthetic and seeded.
+Inputs are resident in HBM before the timed region.  Prints one JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="clustered", choices=["clustered", "mid", "large", "stream1m"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-queries", type=int, default=0, help="oracle sample size (0: 2 per thread)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no collectives); use --gpus 1")
+
+    import torch
+
+    from paper_2603_10846_amd import binding, synth
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: needs a GPU (there is no CPU path)")
+    w = {"clustered": synth.CLUSTERED, "mid": synth.MID, "large": synth.LARGE,
+         "stream1m": synth.scaled(synth.STREAM, N=1048576)}[args.workload]
+    stage = synth.REFINE if args.workload == "large" else synth.DRAFT
+    steps, warm = args.steps, args.warmup
+    dev = torch.device("cuda:0")
+    todev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+
+    t0 = time.time()
+    cap = w.N + (steps + warm + 2) * w.B
+    bank = binding.MemoryBank(w.d, w.dtype, cap, max_B=w.B, max_k1=w.k1)
+    qtab = synth.q_tables(w)
+    need_host_bank = not args.no_cpu_baseline
+    host_rows = np.empty((w.N, w.d), np.float32) if need_host_bank else None
+    for j in range(synth.n_chunks(w)):
+        c = synth.bank_chunk(w, j)
+        a = j * synth.CHUNK_ROWS
+        bank.append(todev(c), todev(qtab[0, a:a + len(c)]), todev(qtab[1, a:a + len(c)]))
+        if need_host_bank:
+            host_rows[a:a + len(c)] = c
+    print(f"# bank built in {time.time() - t0:.1f}s", file=sys.stderr, flush=True)
+
+    # per-step inputs, resident on the device before timing
+    n_total = steps + warm
+    q_host = [synth.queries(w, step=s) for s in range(min(n_total, 8))]
+    q_dev = [todev(q) for q in q_host]
+    new_rows = todev(synth.queries(w, step=1000))                 # entries appended each step
+    rewards = [todev(synth.bernoulli_rewards(w, s, w.B * w.k2)) for s in range(min(n_total, 8))]
+    out = (torch.empty((w.B, w.k2), dtype=torch.int32, device=dev),
+           torch.empty((w.B, w.k2), dtype=torch.float32, device=dev), None, None)
+
+    def step(s):
+        bank.append(new_rows)
+        ids, _, _, _ = bank.retrieve(q_dev[s % len(q_dev)], stage, w.k1, w.k2, w.lam, out=out)
+        bank.update_q(ids.view(-1), stage, rewards[s % len(rewards)], w.alpha)
+
+    for s in range(warm):
+        step(s)
+    torch.cuda.synchronize()
+    bank.profile_enable(True)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for s in range(steps):
+        step(warm + s)
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    prof = bank.profile_read()
+    bank.profile_enable(False)
+    ms_per_step = (t2 - t1) * 1e3 / steps
+    qps = w.B / (ms_per_step * 1e-3)
+
+    # separate timing of the three calls (not part of `value`)
+    def timed(fn, reps=10):
+        torch.cuda.synchronize()
+        a = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - a) * 1e3 / reps
+    ids_fixed = out[0].view(-1).clone()
+    breakdown = {
+        "retrieve_ms": timed(lambda: bank.retrieve(q_dev[0], stage, w.k1, w.k2, w.lam, out=out)),
+        "update_q_ms": timed(lambda: bank.update_q(ids_fixed, stage, rewards[0], w.alpha)),
+    }
+
+    # roofline of the dominant kernel: the densest scan pass (HBM-bound: it must read its rows once)
+    elem = 4 if w.dtype == "f32" else 2
+    dense_rows = max(r for _, r in prof)
+    dense = [ms for ms, r in prof if r == dense_rows]
+    avg_ms = float(np.mean(dense))
+    alg_bytes = dense_rows * w.d * elem
+    achieved = alg_bytes / (avg_ms * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": "k_scan_mfma (densest pass)", "achieved": round(achieved, 1),
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "avg_launch_ms": round(avg_ms, 4), "launches": len(dense), "rows_per_launch": int(dense_rows),
+                "bytes_per_row": w.d * elem,
+                "mfma_tflops": round(2.0 * w.B * dense_rows * w.d / (avg_ms * 1e-3) / 1e12, 1),
+                "all_scan_passes_ms_per_step": round(sum(ms for ms, _ in prof) / steps, 4)}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import oracle as orc
+        threads = min(orc.max_threads(), 16)
+        nq = args.cpu_queries or 2 * threads
+        dt = {"f32": 0, "bf16": 1, "f16": 2}[w.dtype]
+        rounded = orc.round_to_store(host_rows, dt)
+        del host_rows
+        qs = orc.round_to_store(q_host[0][:nq], dt)
+        a = time.perf_counter()
+        res = orc.retrieve(rounded, qs, qtab[stage], w.k1, w.k2, float(np.float32(w.lam)), threads=threads)
+        orc.update_q32(qtab[stage], res["ids"].reshape(-1), np.zeros(res["ids"].size, np.float32), w.alpha)
+        el = time.perf_counter() - a
+        cpu = {"value": round(nq / el, 3), "unit": "queries/s", "cores": threads, "kind": "oracle",
+               "sample": f"{nq} of the {w.B} queries of one step over the full {w.N}-entry bank "
+                         f"(recall + value filter + update), {el:.1f} s"}
+
+    print(json.dumps({
+        "metric": "retrieval queries/sec at N=1M,d=1024 + achieved HBM GB/s (% of peak)"
+                  if args.workload == "clustered" else f"retrieval queries/sec ({args.workload})",
+        "value": round(qps, 1), "unit": "queries/s", "n_gpus": 1, "steps": steps, "warmup": warm,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": {"f32": "f32", "bf16": "bf16", "f16": "f16"}[w.dtype], "data": "synthetic",
+        "config": {"workload": f"{w.name}: N={w.N} d={w.d} {w.dtype} store / fp32 accumulate, B={w.B} k1={w.k1} "
+                               f"k2={w.k2} lambda={w.lam}; step = append B + retrieve B + update_q B*k2",
+                   "N": w.N, "d": w.d, "B": w.B, "k1": w.k1, "k2": w.k2},
+        "roofline": roofline, "cpu_baseline": cpu, "breakdown": breakdown,
+    }))
+    bank.close()
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,154 @@
+/*
+ * evomem -- value-driven memory retrieval on one MI355X (gfx950), C ABI.
+ *
+ * The library implements the retrieval policy mu of Sec. 3.2 of the paper ("Memory Architecture
+ * and Value-Driven Retrieval") over a growing bank of embedded memory items (Sec. 3.1, memory
+ * growth rule):
+ *
+ *   mem_append    M_{t+1} <- M_t u {...}: add entries to the bank (Sec. 3.1, memory update rule).
+ *   mem_retrieve  dense recall of a top-k1 candidate pool by cosine similarity, then the
+ *                 stage-specific value filter down to the final k2 items (Sec. 3.2; k1 is the
+ *                 paper's K, k2 the paper's final retrieval count N).
+ *   mem_update_q  unified Monte-Carlo value update Q <- Q + alpha (r - Q) for the given ids
+ *                 (Sec. 3.2, Eq. "unified update"; App. A, bandit-style update).
+ *
+ * Conventions
+ *   - Every `*_dev` pointer is DEVICE memory owned by the caller (for instance a torch tensor's
+ *     data_ptr) and must stay valid until mem_destroy.  The library owns only its host handle and
+ *     a few HIP events.  Pointers without the suffix are HOST memory.
+ *   - `hip_stream` is a hipStream_t passed as void*; NULL is the default stream.  Calls on one
+ *     stream are ordered; using one handle from several streams at once is not supported.
+ *   - No call synchronises with the host except those documented to do so.
+ *   - Entry ids are dense int32: 0,1,2,... in append order, never reused (the bank only grows).
+ *   - Similarity is the cosine between the STORED vectors: rows and queries are rounded to the
+ *     bank's element type (round-to-nearest-even) first; accumulation is fp32 or wider and the
+ *     similarities that reach the value filter are accumulated in fp64.
+ *   - Order rule in both selections: larger value first, lower id first among equal values.
+ *   - Value filter: score = (1-lambda) z(sim) + lambda z(Q_stage), z being the z-score over the
+ *     query's own candidate pool (population standard deviation, denominator std + 1e-6).
+ *     lambda = 0 ranks by similarity alone, lambda = 1 by the stage's Q alone.
+ *   - All functions return a mem_status; nothing throws or aborts.  NaN or zero-norm inputs give
+ *     unspecified results (not checked on the hot path).
+ */
+#ifndef EVOMEM_H
+#define EVOMEM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct evomem evomem_t; /* opaque host handle */
+
+enum mem_status {
+    MEM_OK = 0,
+    MEM_EINVAL = 1,     /* bad argument (null pointer, bad enum, size out of range, ...) */
+    MEM_ECAPACITY = 2,  /* append would exceed the capacity given at creation; nothing is appended */
+    MEM_EWORKSPACE = 3, /* workspace smaller than mem_workspace_bytes() for the stated maxima */
+    MEM_EHIP = 4,       /* a HIP runtime call failed */
+    MEM_ESTATE = 5      /* handle unusable (e.g. created for another device) */
+};
+enum mem_dtype { MEM_F32 = 0, MEM_BF16 = 1, MEM_F16 = 2 }; /* storage element type */
+enum mem_stage { MEM_STAGE_DRAFT = 0, MEM_STAGE_REFINE = 1 }; /* Q_1 / Q_2 of Sec. 3.2 */
+
+#define MEM_MAX_K1 256   /* largest candidate pool */
+#define MEM_MAX_B 4096   /* largest query batch per call */
+
+/* Bytes the caller must allocate for the embedding store (tiled layout, padded), for given
+ * dimension (multiple of 8, 8..16384), element type and capacity (entries, 1 .. 2^31-257).
+ * Returns 0 on bad arguments. */
+size_t mem_store_bytes(int d, int dtype, int64_t capacity);
+
+/* Bytes of scratch the caller must allocate for calls with B <= max_B and k1 <= max_k1.
+ * Returns 0 on bad arguments. */
+size_t mem_workspace_bytes(int d, int dtype, int64_t capacity, int max_B, int max_k1);
+
+/*
+ * Create an empty bank (Sec. 3.1: M_0 is whatever the caller appends first).  Touches no device
+ * memory except a clear of two counters at the head of the workspace, which it waits for.
+ *   store_dev      mem_store_bytes() bytes, 256-byte aligned
+ *   invnorm_dev    float[capacity rounded up to a multiple of 256]
+ *   q_dev          float[2][capacity]: row 0 = drafting values Q_1, row 1 = refining values Q_2
+ *   workspace_dev  mem_workspace_bytes() bytes, 256-byte aligned
+ *   device         HIP device ordinal the buffers live on
+ * Errors: MEM_EINVAL, MEM_EWORKSPACE, MEM_EHIP.
+ */
+int mem_create(evomem_t** out, int d, int dtype, int64_t capacity,
+               void* store_dev, float* invnorm_dev, float* q_dev,
+               void* workspace_dev, size_t workspace_bytes, int max_B, int max_k1, int device);
+
+/*
+ * Append n entries (Sec. 3.1, memory update rule).  emb_dev: float[n][d] row-major, any norm.
+ * q0_*_dev: float[n] initial values for the two tables, or NULL for 0 (App. A only requires Q_0
+ * inside the reward range).  *first_id_out (host, may be NULL) receives the id of the first new
+ * entry; the rest follow consecutively.  n = 0 is a no-op.
+ * Errors: MEM_EINVAL, MEM_ECAPACITY (bank unchanged), MEM_EHIP.
+ */
+int mem_append(evomem_t* h, const float* emb_dev, int64_t n,
+               const float* q0_draft_dev, const float* q0_refine_dev,
+               int64_t* first_id_out, void* hip_stream);
+
+/*
+ * Retrieve for B queries (Sec. 3.2: top-K pool by dense retrieval, then filter by Q_stage to the
+ * final items).  queries_dev: float[B][d].  With N entries in the bank, k1_eff = min(k1, N) and
+ * k2_eff = min(k2, k1_eff).
+ *   out_ids_dev     int32[B][k2]   final items, best first; unused slots -1
+ *   out_scores_dev  float[B][k2]   their scores; unused slots -inf
+ *   out_cand_ids_dev / out_cand_sims_dev   int32/float [B][k1] the candidate pool ordered by
+ *                   (similarity desc, id asc), or NULL (both or neither); unused slots -1 / -inf
+ * B = 0 is a no-op.  Errors: MEM_EINVAL (null pointers, stage, k1 < 1, k2 < 1, k2 > k1,
+ * k1 > max_k1, B > max_B, lambda outside [0,1] or NaN), MEM_EHIP.
+ */
+int mem_retrieve(evomem_t* h, const float* queries_dev, int B, int stage, int k1, int k2,
+                 float lambda, int32_t* out_ids_dev, float* out_scores_dev,
+                 int32_t* out_cand_ids_dev, float* out_cand_sims_dev, void* hip_stream);
+
+/*
+ * Value update (Sec. 3.2, Eq. "unified update"): for j = 0..M-1 in array order,
+ * Q_stage[ids[j]] <- Q + alpha (rewards[j] - Q), each operation rounded to fp32 (no fused
+ * multiply-add).  An id that occurs several times receives its rewards one after another in array
+ * order (the recursion unrolled in App. A).  Every other entry, and the other stage's table, is
+ * left bit-for-bit unchanged.  Ids outside [0, N) are skipped and counted.  No floating-point
+ * atomics: one writer per distinct id.  M = 0 is a no-op.
+ * Errors: MEM_EINVAL (null pointers, stage, M < 0, alpha outside (0,1] or NaN), MEM_EHIP.
+ */
+int mem_update_q(evomem_t* h, const int32_t* ids_dev, int64_t M, int stage,
+                 const float* rewards_dev, float alpha, void* hip_stream);
+
+/* Number of entries in the bank (host-side counter). */
+int mem_size(const evomem_t* h, int64_t* n_out);
+
+/* Copy Q_stage[first .. first+n) into dst_dev (float[n]).  For tests and export. */
+int mem_read_q(evomem_t* h, int stage, int64_t first, int64_t n, float* dst_dev, void* hip_stream);
+
+/* Copy stored rows first .. first+n, widened to fp32 and un-tiled, into dst_dev (float[n][d]). */
+int mem_read_rows(evomem_t* h, int64_t first, int64_t n, float* dst_dev, void* hip_stream);
+
+/* Synchronises the device.  *skipped_ids: ids mem_update_q skipped so far; *overflows: queries
+ * whose survivor list overflowed during some retrieve (their pool may then be inexact). */
+int mem_counters(evomem_t* h, int64_t* skipped_ids, int64_t* overflows);
+
+/* Per-kernel timing with HIP events on the call's stream (off by default).  While on, every
+ * launch of the similarity-scan kernel is bracketed by two events (at most 4096 launches are kept
+ * between reads).  mem_profile_read synchronises the device and writes, for up to `capacity`
+ * launches recorded since the last read, in launch order: ms_out[i] the duration in milliseconds,
+ * rows_out[i] the number of bank rows that launch scanned; *n_out is how many were written. */
+int mem_profile_enable(evomem_t* h, int on);
+int mem_profile_read(evomem_t* h, int capacity, int* n_out, float* ms_out, int64_t* rows_out);
+
+/* Host only, for tests of the scan plan: the passes a retrieve with pool size k1 makes over a bank of
+ * N entries, sparsest first.  Pass i scans the 256-row tiles t = u * stride[i] (u = 0,1,...) below
+ * ceil(N/256), leaving out those with u % rho[i] == 0 when rho[i] > 0 (a sparser pass owns them);
+ * ntiles[i] is their number.  Returns the number of passes (at most max_levels are written), or -1
+ * on bad arguments. */
+int mem_plan_levels(int64_t N, int k1, int* stride, int* rho, int* ntiles, int max_levels);
+
+const char* mem_strerror(int status);
+int mem_destroy(evomem_t* h);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EVOMEM_H */

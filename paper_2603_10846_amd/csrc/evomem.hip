@@ -1,0 +1,400 @@
+// Host side of the evomem C ABI (include/evomem.h): argument checks, workspace carving, the scan
+// plan, kernel dispatch.  Every step of the method runs in the kernels included below.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#define MEM_MAX_K1_INTERNAL 256
+#include "../../include/evomem.h"
+#include "k_ingest.h"
+#include "k_scan_gemv.h"
+#include "k_scan_mfma.h"
+#include "k_select.h"
+#include "k_update.h"
+#include "layout.h"
+
+using namespace evk;
+
+static_assert(MEM_MAX_K1 == MEM_MAX_K1_INTERNAL, "header and kernels disagree on the largest pool");
+
+namespace {
+
+constexpr int MAX_PROFILE = 4096;
+constexpr int GEMV_MAX_B = 4;       // at most this many queries use the VALU scan
+
+inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+struct Workspace {   // byte offsets into the caller's workspace
+    size_t counters, qf, qop, invq, invq64, thr, cnt, surv, exact, total;
+};
+
+Workspace carve(int d, int dtype, int max_B) {
+    const int64_t dpad = round_up(d, KB), Bp = round_up(max_B, 256);
+    Workspace w{};
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = (size_t)round_up((int64_t)(o + bytes), 256); return at; };
+    w.counters = take(256);
+    w.qf = take((size_t)Bp * dpad * 4);
+    w.qop = take((size_t)Bp * dpad * (dtype == MEM_F32 ? 4 : 2));
+    w.invq = take((size_t)Bp * 4);
+    w.invq64 = take((size_t)Bp * 8);
+    w.thr = take((size_t)Bp * 4);
+    w.cnt = take((size_t)Bp * 4);
+    w.surv = take((size_t)Bp * SURV_CAP * 8);
+    w.exact = take((size_t)Bp * KEEP_MAX * 8);
+    w.total = o;
+    return w;
+}
+
+bool shape_ok(int d, int dtype, int64_t capacity) {
+    return d >= 8 && d <= 16384 && d % 8 == 0 && dtype >= MEM_F32 && dtype <= MEM_F16 && capacity >= 1 &&
+           capacity <= 2147483647ll - 256;
+}
+
+}  // namespace
+
+struct evomem {
+    int d, dtype, nkb, device, max_B, max_k1;
+    int64_t capacity, N;
+    void* store;
+    float* invnorm;
+    float* q;
+    unsigned char* ws;
+    Workspace w;
+    bool lds_attr_set;
+    // profiling
+    bool prof_on;
+    int prof_n;
+    std::vector<hipEvent_t> ev;
+    std::vector<int64_t> prof_rows;
+};
+
+#define HIPCHK(x) do { if ((x) != hipSuccess) return MEM_EHIP; } while (0)
+#define LAUNCHCHK() do { if (hipGetLastError() != hipSuccess) return MEM_EHIP; } while (0)
+
+extern "C" {
+
+size_t mem_store_bytes(int d, int dtype, int64_t capacity) {
+    if (!shape_ok(d, dtype, capacity)) return 0;
+    return (size_t)round_up(capacity, TILE_ROWS) * (size_t)round_up(d, KB) * (dtype == MEM_F32 ? 4 : 2);
+}
+
+size_t mem_workspace_bytes(int d, int dtype, int64_t capacity, int max_B, int max_k1) {
+    if (!shape_ok(d, dtype, capacity) || max_B < 1 || max_B > MEM_MAX_B || max_k1 < 1 || max_k1 > MEM_MAX_K1) return 0;
+    return carve(d, dtype, max_B).total;
+}
+
+int mem_create(evomem_t** out, int d, int dtype, int64_t capacity, void* store_dev, float* invnorm_dev,
+               float* q_dev, void* workspace_dev, size_t workspace_bytes, int max_B, int max_k1, int device) {
+    if (!out) return MEM_EINVAL;
+    *out = nullptr;
+    if (!shape_ok(d, dtype, capacity) || !store_dev || !invnorm_dev || !q_dev || !workspace_dev) return MEM_EINVAL;
+    if (max_B < 1 || max_B > MEM_MAX_B || max_k1 < 1 || max_k1 > MEM_MAX_K1 || device < 0) return MEM_EINVAL;
+    if (((uintptr_t)store_dev | (uintptr_t)workspace_dev) & 255) return MEM_EINVAL;
+    Workspace w = carve(d, dtype, max_B);
+    if (workspace_bytes < w.total) return MEM_EWORKSPACE;
+    evomem* h = new (std::nothrow) evomem();
+    if (!h) return MEM_EHIP;
+    h->d = d; h->dtype = dtype; h->nkb = (int)(round_up(d, KB) / KB); h->device = device;
+    h->max_B = max_B; h->max_k1 = max_k1; h->capacity = capacity; h->N = 0;
+    h->store = store_dev; h->invnorm = invnorm_dev; h->q = q_dev;
+    h->ws = static_cast<unsigned char*>(workspace_dev); h->w = w;
+    h->lds_attr_set = false; h->prof_on = false; h->prof_n = 0;
+    if (hipSetDevice(device) != hipSuccess || hipMemsetAsync(h->ws + w.counters, 0, 256, nullptr) != hipSuccess ||
+        hipStreamSynchronize(nullptr) != hipSuccess) {
+        delete h;
+        return MEM_EHIP;
+    }
+    *out = h;
+    return MEM_OK;
+}
+
+int mem_destroy(evomem_t* h) {
+    if (!h) return MEM_EINVAL;
+    for (hipEvent_t e : h->ev) (void)hipEventDestroy(e);
+    delete h;
+    return MEM_OK;
+}
+
+int mem_size(const evomem_t* h, int64_t* n_out) {
+    if (!h || !n_out) return MEM_EINVAL;
+    *n_out = h->N;
+    return MEM_OK;
+}
+
+int mem_append(evomem_t* h, const float* emb_dev, int64_t n, const float* q0d, const float* q0r,
+               int64_t* first_id_out, void* hip_stream) {
+    if (!h || n < 0 || (n > 0 && !emb_dev)) return MEM_EINVAL;
+    if (h->N + n > h->capacity) return MEM_ECAPACITY;
+    if (first_id_out) *first_id_out = h->N;
+    if (n == 0) return MEM_OK;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    dim3 grid((unsigned)((n + 3) / 4)), block(256);
+    if (h->dtype == MEM_F32)
+        hipLaunchKernelGGL(k_append32, grid, block, 0, st, emb_dev, n, h->d, h->nkb, h->N, (float*)h->store,
+                           h->invnorm, h->q, h->capacity, q0d, q0r);
+    else if (h->dtype == MEM_BF16)
+        hipLaunchKernelGGL(k_append16<BF16>, grid, block, 0, st, emb_dev, n, h->d, h->nkb, h->N, (uint16_t*)h->store,
+                           h->invnorm, h->q, h->capacity, q0d, q0r);
+    else
+        hipLaunchKernelGGL(k_append16<F16>, grid, block, 0, st, emb_dev, n, h->d, h->nkb, h->N, (uint16_t*)h->store,
+                           h->invnorm, h->q, h->capacity, q0d, q0r);
+    LAUNCHCHK();
+    h->N += n;
+    return MEM_OK;
+}
+
+int mem_read_q(evomem_t* h, int stage, int64_t first, int64_t n, float* dst_dev, void* hip_stream) {
+    if (!h || (stage != 0 && stage != 1) || first < 0 || n < 0 || first + n > h->N || (n > 0 && !dst_dev)) return MEM_EINVAL;
+    if (n == 0) return MEM_OK;
+    HIPCHK(hipMemcpyAsync(dst_dev, h->q + stage * h->capacity + first, (size_t)n * 4, hipMemcpyDeviceToDevice,
+                          static_cast<hipStream_t>(hip_stream)));
+    return MEM_OK;
+}
+
+int mem_read_rows(evomem_t* h, int64_t first, int64_t n, float* dst_dev, void* hip_stream) {
+    if (!h || first < 0 || n < 0 || first + n > h->N || (n > 0 && !dst_dev)) return MEM_EINVAL;
+    if (n == 0) return MEM_OK;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    dim3 grid((unsigned)((n + 3) / 4)), block(256);
+    if (h->dtype == MEM_F32)
+        hipLaunchKernelGGL(k_read_rows32, grid, block, 0, st, (const float*)h->store, first, n, h->d, h->nkb, dst_dev);
+    else if (h->dtype == MEM_BF16)
+        hipLaunchKernelGGL(k_read_rows16<BF16>, grid, block, 0, st, (const uint16_t*)h->store, first, n, h->d, h->nkb, dst_dev);
+    else
+        hipLaunchKernelGGL(k_read_rows16<F16>, grid, block, 0, st, (const uint16_t*)h->store, first, n, h->d, h->nkb, dst_dev);
+    LAUNCHCHK();
+    return MEM_OK;
+}
+
+int mem_counters(evomem_t* h, int64_t* skipped_ids, int64_t* overflows) {
+    if (!h) return MEM_EINVAL;
+    uint32_t c[2] = {0, 0};
+    HIPCHK(hipDeviceSynchronize());
+    HIPCHK(hipMemcpy(c, h->ws + h->w.counters, 8, hipMemcpyDeviceToHost));
+    if (skipped_ids) *skipped_ids = c[0];
+    if (overflows) *overflows = c[1];
+    return MEM_OK;
+}
+
+int mem_profile_enable(evomem_t* h, int on) {
+    if (!h) return MEM_EINVAL;
+    if (on && h->ev.empty()) {
+        h->ev.resize(2 * MAX_PROFILE);
+        h->prof_rows.resize(MAX_PROFILE);
+        for (auto& e : h->ev)
+            if (hipEventCreate(&e) != hipSuccess) return MEM_EHIP;
+    }
+    h->prof_on = on != 0;
+    h->prof_n = 0;
+    return MEM_OK;
+}
+
+int mem_profile_read(evomem_t* h, int capacity, int* n_out, float* ms_out, int64_t* rows_out) {
+    if (!h || capacity < 0 || !n_out || (capacity > 0 && (!ms_out || !rows_out))) return MEM_EINVAL;
+    HIPCHK(hipDeviceSynchronize());
+    int n = h->prof_n < capacity ? h->prof_n : capacity;
+    for (int i = 0; i < n; ++i) {
+        HIPCHK(hipEventElapsedTime(&ms_out[i], h->ev[2 * i], h->ev[2 * i + 1]));
+        rows_out[i] = h->prof_rows[i];
+    }
+    *n_out = n;
+    h->prof_n = 0;
+    return MEM_OK;
+}
+
+const char* mem_strerror(int s) {
+    switch (s) {
+        case MEM_OK: return "ok";
+        case MEM_EINVAL: return "invalid argument";
+        case MEM_ECAPACITY: return "bank capacity exceeded";
+        case MEM_EWORKSPACE: return "workspace too small";
+        case MEM_EHIP: return "HIP runtime error";
+        case MEM_ESTATE: return "handle in unusable state";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"
+
+namespace {
+
+// Scan plan: tile strides of the passes, sparsest first.  The sparsest pass has no threshold, so it
+// may cover at most SURV_CAP rows; each denser pass divides the stride by `ratio`, chosen so that
+// about k1 * ratio rows (a quarter of the survivor slots) are expected to pass its threshold.
+std::vector<Level> plan_levels(int64_t N, int k1) {
+    const int nt = (int)((N + TILE_ROWS - 1) / TILE_ROWS);
+    int ratio = SURV_CAP / (4 * k1);
+    if (ratio > 16) ratio = 16;
+    if (ratio < 2) ratio = 2;
+    std::vector<int> strides{1};
+    while ((nt + strides.back() - 1) / strides.back() > SURV_CAP / TILE_ROWS) strides.push_back(strides.back() * ratio);
+    std::vector<Level> lv;
+    for (int i = (int)strides.size() - 1; i >= 0; --i) {
+        Level L;
+        L.stride = strides[i];
+        const int U = (nt + L.stride - 1) / L.stride;
+        if (i == (int)strides.size() - 1) { L.rho = 0; L.ntiles = U; }
+        else { L.rho = ratio; L.ntiles = U - (U + ratio - 1) / ratio; }
+        if (L.ntiles > 0) lv.push_back(L);
+    }
+    return lv;
+}
+
+template <int DT, int MQ, int WQ, int MR, int WR>
+int launch_mfma(evomem* h, hipStream_t st, int Bp, const Level& L) {
+    constexpr int QT = 32 * MQ * WQ;
+    constexpr int lds = scan_mfma_lds_bytes<QT>();
+    auto kern = k_scan_mfma<DT, MQ, WQ, MR, WR>;
+    static bool attr_done[16] = {};
+    if (!attr_done[h->device & 15]) {
+        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+        attr_done[h->device & 15] = true;
+    }
+    const int nqt = Bp / QT;
+    dim3 grid((unsigned)(8 * ((L.ntiles + 7) / 8) * nqt)), block(256);
+    unsigned char* ws = h->ws;
+    hipLaunchKernelGGL(kern, grid, block, lds, st, (const void*)h->store, (const float*)h->invnorm,
+                       (const uint16_t*)(ws + h->w.qop), (const float*)(ws + h->w.invq), (const float*)(ws + h->w.thr),
+                       (uint32_t*)(ws + h->w.cnt), (uint64_t*)(ws + h->w.surv), h->N, h->nkb, Bp, L);
+    LAUNCHCHK();
+    return MEM_OK;
+}
+
+template <int DT>
+int launch_mfma_dt(evomem* h, hipStream_t st, int Bp, int qt, const Level& L) {
+    switch (qt) {
+        case 32: return launch_mfma<DT, 1, 1, 2, 4>(h, st, Bp, L);
+        case 64: return launch_mfma<DT, 2, 1, 2, 4>(h, st, Bp, L);
+        case 128: return launch_mfma<DT, 2, 2, 4, 2>(h, st, Bp, L);
+        default: return launch_mfma<DT, 4, 2, 4, 2>(h, st, Bp, L);
+    }
+}
+
+template <int NB>
+int launch_gemv(evomem* h, hipStream_t st, int B, const Level& L) {
+    unsigned char* ws = h->ws;
+    dim3 grid((unsigned)L.ntiles), block(256);
+    const float* invq = (const float*)(ws + h->w.invq);
+    const float* thr = (const float*)(ws + h->w.thr);
+    const float* qf = (const float*)(ws + h->w.qf);
+    uint32_t* cnt = (uint32_t*)(ws + h->w.cnt);
+    uint64_t* surv = (uint64_t*)(ws + h->w.surv);
+    if (h->dtype == MEM_F32)
+        hipLaunchKernelGGL(k_scan_gemv32<NB>, grid, block, 0, st, (const float*)h->store, (const float*)h->invnorm, qf, invq,
+                           thr, cnt, surv, h->N, h->nkb, B, L);
+    else if (h->dtype == MEM_BF16)
+        hipLaunchKernelGGL((k_scan_gemv16<BF16, NB>), grid, block, 0, st, (const uint16_t*)h->store, (const float*)h->invnorm,
+                           qf, invq, thr, cnt, surv, h->N, h->nkb, B, L);
+    else
+        hipLaunchKernelGGL((k_scan_gemv16<F16, NB>), grid, block, 0, st, (const uint16_t*)h->store, (const float*)h->invnorm,
+                           qf, invq, thr, cnt, surv, h->N, h->nkb, B, L);
+    LAUNCHCHK();
+    return MEM_OK;
+}
+
+}  // namespace
+
+extern "C" int mem_plan_levels(int64_t N, int k1, int* stride, int* rho, int* ntiles, int max_levels) {
+    if (N < 1 || N > 2147483647ll - 256 || k1 < 1 || k1 > MEM_MAX_K1 || !stride || !rho || !ntiles || max_levels < 1) return -1;
+    std::vector<Level> lv = plan_levels(N, k1);
+    for (int i = 0; i < (int)lv.size() && i < max_levels; ++i) { stride[i] = lv[i].stride; rho[i] = lv[i].rho; ntiles[i] = lv[i].ntiles; }
+    return (int)lv.size();
+}
+
+extern "C" int mem_retrieve(evomem_t* h, const float* queries_dev, int B, int stage, int k1, int k2, float lambda,
+                            int32_t* out_ids_dev, float* out_scores_dev, int32_t* out_cand_ids_dev,
+                            float* out_cand_sims_dev, void* hip_stream) {
+    if (!h || B < 0 || B > h->max_B || (stage != 0 && stage != 1) || k1 < 1 || k2 < 1 || k2 > k1 || k1 > h->max_k1)
+        return MEM_EINVAL;
+    if (!(lambda >= 0.f && lambda <= 1.f)) return MEM_EINVAL;
+    if ((out_cand_ids_dev == nullptr) != (out_cand_sims_dev == nullptr)) return MEM_EINVAL;
+    if (B == 0) return MEM_OK;
+    if (!queries_dev || !out_ids_dev || !out_scores_dev) return MEM_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    unsigned char* ws = h->ws;
+    const bool gemv = B <= GEMV_MAX_B;
+    // query tile of the MFMA scan and padded batch
+    int qt = B <= 32 ? 32 : B <= 64 ? 64 : B <= 128 ? 128 : 256;
+    const int Bp = gemv ? B : (int)round_up(B, qt);
+    float* qf = (float*)(ws + h->w.qf);
+    uint16_t* qop = (uint16_t*)(ws + h->w.qop);
+    float* invq = (float*)(ws + h->w.invq);
+    double* invq64 = (double*)(ws + h->w.invq64);
+    float* thr = (float*)(ws + h->w.thr);
+    uint32_t* cnt = (uint32_t*)(ws + h->w.cnt);
+    uint64_t* surv = (uint64_t*)(ws + h->w.surv);
+    double* exact = (double*)(ws + h->w.exact);
+    uint32_t* counters = (uint32_t*)(ws + h->w.counters);
+
+    if (h->dtype == MEM_F32)
+        hipLaunchKernelGGL(k_prep_queries<0>, dim3(Bp), dim3(256), 0, st, queries_dev, B, Bp, h->d, h->nkb, qf, qop, invq, invq64, thr, cnt);
+    else if (h->dtype == MEM_BF16)
+        hipLaunchKernelGGL(k_prep_queries<1>, dim3(Bp), dim3(256), 0, st, queries_dev, B, Bp, h->d, h->nkb, qf, qop, invq, invq64, thr, cnt);
+    else
+        hipLaunchKernelGGL(k_prep_queries<2>, dim3(Bp), dim3(256), 0, st, queries_dev, B, Bp, h->d, h->nkb, qf, qop, invq, invq64, thr, cnt);
+    LAUNCHCHK();
+
+    // guard band of the selected list and rounding margin of the scan's fp32 similarities
+    int keep = k1 + (k1 / 2 > 32 ? k1 / 2 : 32);
+    if (keep > KEEP_MAX) keep = KEEP_MAX;
+    float eps = (float)(h->nkb * KB) * 5.97e-8f + 1e-6f;
+    if (h->dtype == MEM_F32 && !gemv) eps += 2e-5f;      // bf16 hi/lo split of fp32 values
+    const float margin = 2.f * eps;
+
+    if (h->N > 0) {
+        std::vector<Level> levels = plan_levels(h->N, k1);
+        for (const Level& L : levels) {
+            const bool prof = h->prof_on && h->prof_n < MAX_PROFILE;
+            if (prof) HIPCHK(hipEventRecord(h->ev[2 * h->prof_n], st));
+            int rc;
+            if (gemv) {
+                rc = B == 1 ? launch_gemv<1>(h, st, B, L) : B == 2 ? launch_gemv<2>(h, st, B, L) : launch_gemv<4>(h, st, B, L);
+            } else {
+                rc = h->dtype == MEM_F32 ? launch_mfma_dt<0>(h, st, Bp, qt, L)
+                   : h->dtype == MEM_BF16 ? launch_mfma_dt<1>(h, st, Bp, qt, L) : launch_mfma_dt<2>(h, st, Bp, qt, L);
+            }
+            if (rc != MEM_OK) return rc;
+            if (prof) {
+                HIPCHK(hipEventRecord(h->ev[2 * h->prof_n + 1], st));
+                int64_t rows = (int64_t)L.ntiles * TILE_ROWS;
+                h->prof_rows[h->prof_n++] = rows;
+            }
+            hipLaunchKernelGGL(k_select, dim3(B), dim3(1024), 0, st, surv, cnt, thr, (const float*)invq, counters, k1, keep, margin);
+            LAUNCHCHK();
+        }
+        dim3 rgrid((unsigned)((keep + 3) / 4), (unsigned)B);
+        if (h->dtype == MEM_F32)
+            hipLaunchKernelGGL(k_rescore<0>, rgrid, dim3(256), 0, st, (const void*)h->store, (const float*)qf, (const double*)invq64, (const uint64_t*)surv, (const uint32_t*)cnt, exact, h->nkb);
+        else if (h->dtype == MEM_BF16)
+            hipLaunchKernelGGL(k_rescore<1>, rgrid, dim3(256), 0, st, (const void*)h->store, (const float*)qf, (const double*)invq64, (const uint64_t*)surv, (const uint32_t*)cnt, exact, h->nkb);
+        else
+            hipLaunchKernelGGL(k_rescore<2>, rgrid, dim3(256), 0, st, (const void*)h->store, (const float*)qf, (const double*)invq64, (const uint64_t*)surv, (const uint32_t*)cnt, exact, h->nkb);
+        LAUNCHCHK();
+    }
+    hipLaunchKernelGGL(k_rerank, dim3(B), dim3(256), 0, st, (const uint64_t*)surv, (const uint32_t*)cnt, (const double*)exact,
+                       (const float*)(h->q + (int64_t)stage * h->capacity), k1, k2, (double)lambda, out_ids_dev, out_scores_dev,
+                       out_cand_ids_dev, out_cand_sims_dev);
+    LAUNCHCHK();
+    return MEM_OK;
+}
+
+extern "C" int mem_update_q(evomem_t* h, const int32_t* ids_dev, int64_t M, int stage, const float* rewards_dev,
+                            float alpha, void* hip_stream) {
+    if (!h || M < 0 || (stage != 0 && stage != 1) || !(alpha > 0.f && alpha <= 1.f)) return MEM_EINVAL;
+    if (M == 0) return MEM_OK;
+    if (!ids_dev || !rewards_dev) return MEM_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    uint32_t* counters = (uint32_t*)(h->ws + h->w.counters);
+    for (int64_t off = 0; off < M; off += UPD_CHUNK) {
+        int m = (int)(M - off < UPD_CHUNK ? M - off : UPD_CHUNK);
+        hipLaunchKernelGGL(k_update_q, dim3(1), dim3(1024), 0, st, ids_dev + off, rewards_dev + off, m,
+                           h->q + (int64_t)stage * h->capacity, h->N, alpha, counters);
+        LAUNCHCHK();
+    }
+    return MEM_OK;
+}

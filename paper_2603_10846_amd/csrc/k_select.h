@@ -1,0 +1,168 @@
+// Selection kernels: survivor lists -> candidate pool -> value filter (Sec. 3.2).
+#pragma once
+#include "k_ingest.h"
+#include "layout.h"
+
+namespace evk {
+
+// In-LDS bitonic sort, descending, n a power of two, all threads of the workgroup take part.
+template <typename T, typename Less>
+__device__ __forceinline__ void bitonic_desc(T* a, int n, int tid, int nthreads, Less less) {
+    for (int k = 2; k <= n; k <<= 1)
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int p = tid; p < (n >> 1); p += nthreads) {
+                int i = ((p & ~(j - 1)) << 1) | (p & (j - 1));   // index with bit j clear
+                int l = i | j;
+                bool desc = (i & k) == 0;
+                T x = a[i], y = a[l];
+                if (less(x, y) == desc) { a[i] = y; a[l] = x; }
+            }
+            __syncthreads();
+        }
+}
+
+// After a scan pass: order the query's survivors by (similarity desc, id asc), keep the best `keep`
+// (k1 plus a guard band) at the head of its list as the seed of the next pass, and set the next
+// pass's threshold to the k1-th best similarity minus `margin` (a bound on the scan's rounding
+// error, so that no true member of the pool can be filtered out), pre-divided by the query's
+// inverse norm because the scan compares before applying it.  One workgroup per query.
+__global__ __launch_bounds__(1024) void k_select(uint64_t* __restrict__ surv, uint32_t* __restrict__ cnt,
+                                                 float* __restrict__ thr, const float* __restrict__ invq,
+                                                 uint32_t* __restrict__ counters, int k1, int keep, float margin) {
+    __shared__ uint64_t keys[SURV_CAP];
+    const int b = blockIdx.x, tid = threadIdx.x;
+    uint64_t* list = surv + (int64_t)b * SURV_CAP;
+    uint32_t raw = cnt[b];
+    int n = raw > (uint32_t)SURV_CAP ? SURV_CAP : (int)raw;
+    if (raw > (uint32_t)SURV_CAP && tid == 0) atomicAdd(counters + 1, 1u);
+    int npad = 2;
+    while (npad < n) npad <<= 1;
+    for (int i = tid; i < npad; i += 1024) keys[i] = i < n ? list[i] : 0ull;
+    __syncthreads();
+    bitonic_desc(keys, npad, tid, 1024, [](uint64_t x, uint64_t y) { return x < y; });
+    int kk = n < keep ? n : keep;
+    for (int i = tid; i < kk; i += 1024) list[i] = keys[i];
+    if (tid == 0) {
+        cnt[b] = (uint32_t)kk;
+        float t = -INFINITY;
+        if (n >= k1) t = (key_sim(keys[k1 - 1]) - margin) / invq[b];
+        thr[b] = t;
+    }
+}
+
+// Exact similarities of the selected candidates: one wavefront per (query, candidate) re-reads the
+// stored row and accumulates dot product and squared norm in fp64 (products of 16-bit values are
+// exact, so this is the cosine of the stored vectors up to fp64 rounding).
+template <int DT>
+__global__ __launch_bounds__(256) void k_rescore(const void* __restrict__ store_, const float* __restrict__ qf,
+                                                 const double* __restrict__ invq64, const uint64_t* __restrict__ surv,
+                                                 const uint32_t* __restrict__ cnt, double* __restrict__ exact,
+                                                 int nkb) {
+    const int b = blockIdx.y, lane = threadIdx.x & 63;
+    const int j = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (j >= (int)cnt[b]) return;
+    const int32_t id = key_id(surv[(int64_t)b * SURV_CAP + j]);
+    const float* q = qf + (int64_t)b * nkb * KB;
+    double dot = 0.0, ssq = 0.0;
+    if (DT == 0) {
+        const float* store = static_cast<const float*>(store_);
+        for (int c4 = lane; c4 < nkb * 16; c4 += 64) {
+            float4 x = *reinterpret_cast<const float4*>(store + off32(id, c4, nkb));
+            float4 y = *reinterpret_cast<const float4*>(q + c4 * 4);
+            dot += (double)x.x * y.x + (double)x.y * y.y + (double)x.z * y.z + (double)x.w * y.w;
+            ssq += (double)x.x * x.x + (double)x.y * x.y + (double)x.z * x.z + (double)x.w * x.w;
+        }
+    } else {
+        const uint16_t* store = static_cast<const uint16_t*>(store_);
+        for (int c8 = lane; c8 < nkb * 8; c8 += 64) {
+            uint4 pk = *reinterpret_cast<const uint4*>(store + off16(id, c8, nkb));
+            uint32_t w[4] = {pk.x, pk.y, pk.z, pk.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                uint16_t lo = (uint16_t)(w[i] & 0xffff), hi = (uint16_t)(w[i] >> 16);
+                double x0 = DT == 1 ? bf16_to_f(lo) : f16_to_f(lo);
+                double x1 = DT == 1 ? bf16_to_f(hi) : f16_to_f(hi);
+                dot += x0 * (double)q[c8 * 8 + 2 * i] + x1 * (double)q[c8 * 8 + 2 * i + 1];
+                ssq += x0 * x0 + x1 * x1;
+            }
+        }
+    }
+    dot = wave_sum_d(dot);
+    ssq = wave_sum_d(ssq);
+    if (lane == 0) exact[(int64_t)b * KEEP_MAX + j] = dot * invq64[b] * (1.0 / sqrt(ssq));
+}
+
+struct SimId { double v; int32_t id; };
+__device__ __forceinline__ bool simid_less(const SimId& x, const SimId& y) {   // "x ranks below y"
+    return x.v < y.v || (x.v == y.v && x.id > y.id);
+}
+
+// Deterministic sum of f(j), j < n, over a 256-thread workgroup (fixed tree).
+template <typename F>
+__device__ __forceinline__ double block_sum(double* red, int tid, int n, F f) {
+    double s = 0.0;
+    for (int j = tid; j < n; j += 256) s += f(j);
+    red[tid] = s;
+    __syncthreads();
+    for (int st = 128; st > 0; st >>= 1) { if (tid < st) red[tid] += red[tid + st]; __syncthreads(); }
+    double r = red[0];
+    __syncthreads();
+    return r;
+}
+
+// Candidate pool and value filter for one query (Sec. 3.2): order the re-scored candidates by
+// (similarity desc, id asc), keep k1 as the pool C(x); gather the stage's Q values; z-score both
+// over the pool (population deviation, denominator std + 1e-6); score = (1-lambda) z_s + lambda z_q;
+// emit the k2 best by (score desc, id asc).  All in fp64, scores rounded to fp32 on output.
+__global__ __launch_bounds__(256) void k_rerank(const uint64_t* __restrict__ surv, const uint32_t* __restrict__ cnt,
+                                                const double* __restrict__ exact, const float* __restrict__ qstage,
+                                                int k1, int k2, double lambda, int32_t* __restrict__ out_ids,
+                                                float* __restrict__ out_scores, int32_t* __restrict__ cand_ids,
+                                                float* __restrict__ cand_sims) {
+    __shared__ SimId a[KEEP_MAX];
+    __shared__ double qv[MEM_MAX_K1_INTERNAL];
+    __shared__ double red[256];
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const int kk = (int)cnt[b];
+    for (int i = tid; i < KEEP_MAX; i += 256) {
+        SimId e;
+        if (i < kk) { e.v = exact[(int64_t)b * KEEP_MAX + i]; e.id = key_id(surv[(int64_t)b * SURV_CAP + i]); }
+        else        { e.v = -INFINITY; e.id = 0x7fffffff; }
+        a[i] = e;
+    }
+    __syncthreads();
+    bitonic_desc(a, KEEP_MAX, tid, 256, simid_less);
+    const int k1e = kk < k1 ? kk : k1;
+    if (cand_ids)
+        for (int i = tid; i < k1; i += 256) {
+            cand_ids[(int64_t)b * k1 + i] = i < k1e ? a[i].id : -1;
+            cand_sims[(int64_t)b * k1 + i] = i < k1e ? (float)a[i].v : -INFINITY;
+        }
+    for (int i = tid; i < k1e; i += 256) qv[i] = (double)qstage[a[i].id];
+    __syncthreads();
+    double scale_s = 0.0, scale_q = 0.0, mean_s = 0.0, mean_q = 0.0;
+    if (k1e > 0) {
+        mean_s = block_sum(red, tid, k1e, [&](int j) { return a[j].v; }) / k1e;
+        mean_q = block_sum(red, tid, k1e, [&](int j) { return qv[j]; }) / k1e;
+        double var_s = block_sum(red, tid, k1e, [&](int j) { double x = a[j].v - mean_s; return x * x; }) / k1e;
+        double var_q = block_sum(red, tid, k1e, [&](int j) { double x = qv[j] - mean_q; return x * x; }) / k1e;
+        scale_s = 1.0 / (sqrt(var_s) + 1e-6);
+        scale_q = 1.0 / (sqrt(var_q) + 1e-6);
+    }
+    // scores overwrite the similarities of the pool; the rest of the array becomes padding
+    for (int i = tid; i < KEEP_MAX; i += 256) {
+        SimId e = a[i];
+        if (i < k1e) e.v = (1.0 - lambda) * ((e.v - mean_s) * scale_s) + lambda * ((qv[i] - mean_q) * scale_q);
+        else { e.v = -INFINITY; e.id = 0x7fffffff; }
+        a[i] = e;
+    }
+    __syncthreads();
+    bitonic_desc(a, MEM_MAX_K1_INTERNAL, tid, 256, simid_less);
+    const int k2e = k1e < k2 ? k1e : k2;
+    for (int i = tid; i < k2; i += 256) {
+        out_ids[(int64_t)b * k2 + i] = i < k2e ? a[i].id : -1;
+        out_scores[(int64_t)b * k2 + i] = i < k2e ? (float)a[i].v : -INFINITY;
+    }
+}
+
+}  // namespace evk

@@ -1,0 +1,326 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle on the same seeded
+inputs.  Ids bit-exact (lower id breaks ties; a swap is accepted only between entries whose oracle
+values differ by < 1e-5), scores within 1e-5 * max(1,|score|), Q tables bit-exact against the
+sequential fp32 recurrence and within 1e-6 of the fp64 one."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2603_10846_amd import binding as B
+from paper_2603_10846_amd import synth
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+DT = {"f32": 0, "bf16": 1, "f16": 2}
+
+
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def _unit(rng, n, d):
+    x = rng.standard_normal((n, d)).astype(np.float32)
+    return (x / np.linalg.norm(x, axis=1, keepdims=True)).astype(np.float32)
+
+
+def _make_bank(dtype, rows, qtab=None, capacity=None, max_B=1024, max_k1=256, chunk=65536):
+    N, d = rows.shape
+    bank = B.MemoryBank(d, dtype, capacity or max(N, 1), max_B=max_B, max_k1=max_k1)
+    for a in range(0, N, chunk):
+        sl = slice(a, min(N, a + chunk))
+        first = bank.append(_dev(rows[sl]),
+                            None if qtab is None else _dev(qtab[0, sl]),
+                            None if qtab is None else _dev(qtab[1, sl]))
+        assert first == a
+    return bank
+
+
+# ----------------------------------------------------------------------------- store
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+def test_store_holds_rne_rounded_rows(orc, dtype):
+    rng = np.random.default_rng(100)
+    rows = (rng.standard_normal((1000, 72)) * rng.uniform(1e-3, 50, (1000, 1))).astype(np.float32)
+    rows[3, :5] = [65519.9, 65520.0, 1e-8, 6.1e-5, -3.0e-8]      # fp16 overflow edge / subnormals
+    bank = B.MemoryBank(72, dtype, 1000, max_B=8, max_k1=16)
+    assert bank.append(_dev(rows[:600])) == 0 and bank.append(_dev(rows[600:])) == 600
+    assert bank.size() == 1000
+    got = bank.read_rows(0, 1000).cpu().numpy()
+    want = orc.round_to_store(rows, DT[dtype])
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+    assert np.array_equal(bank.read_rows(599, 3).cpu().numpy(), want[599:602])
+    with pytest.raises(B.MemError) as e:
+        bank.append(_dev(rows[:1]))
+    assert e.value.status == B.MEM_ECAPACITY and bank.size() == 1000
+    assert np.all(bank.read_q(0).cpu().numpy() == 0) and np.all(bank.read_q(1).cpu().numpy() == 0)
+    bank.close()
+
+
+# ----------------------------------------------------------------------------- retrieval, small
+
+CASES = [
+    # dtype, N, d, B, k1, k2, lam, stage
+    ("bf16", 5000, 128, 3, 32, 4, 0.5, 0),      # VALU scan, one pass, ragged last tile
+    ("f16", 20000, 256, 2, 16, 16, 0.3, 1),     # VALU scan, two passes
+    ("f32", 3000, 72, 4, 64, 8, 0.7, 0),        # VALU scan fp32, dimension padded to 128
+    ("f32", 9000, 64, 1, 256, 32, 1.0, 1),      # largest pool
+    ("bf16", 20000, 192, 5, 32, 4, 0.5, 0),     # MFMA scan, 32-query tile
+    ("f16", 9000, 64, 40, 8, 2, 0.0, 1),        # MFMA scan, 64-query tile
+    ("bf16", 30000, 256, 100, 64, 8, 0.25, 0),  # MFMA scan, 128-query tile
+    ("bf16", 12345, 128, 260, 128, 16, 0.5, 1), # MFMA scan, two 256-query tiles
+    ("f32", 20000, 128, 33, 64, 8, 0.5, 0),     # MFMA scan on fp32 rows (bf16 hi/lo split)
+    ("f16", 70000, 64, 17, 256, 32, 0.7, 1),    # three passes (ratio 8 at k1 = 256)
+]
+
+
+@pytest.mark.parametrize("dtype,N,d,nq,k1,k2,lam,stage", CASES)
+def test_retrieve_matches_oracle(orc, dtype, N, d, nq, k1, k2, lam, stage):
+    rng = np.random.default_rng([DT[dtype], N, d, nq])
+    rows = _unit(rng, N, d) * rng.uniform(0.5, 2.0, (N, 1)).astype(np.float32)   # norms must not matter
+    rows[N // 2] = rows[7]                                                        # an exact duplicate row
+    queries = _unit(rng, nq, d)
+    queries[0] = rows[7] * np.float32(0.5)                                        # hits the duplicate pair
+    qtab = rng.uniform(-1, 1, (2, N)).astype(np.float32)
+    print(f"case {dtype} N={N} d={d} B={nq} k1={k1} k2={k2}", flush=True)
+    bank = _make_bank(dtype, rows, qtab, max_B=max(nq, 8), max_k1=256)
+    gpu = parity.gpu_retrieve(bank, torch, queries, stage, k1, k2, lam)
+    st = orc.round_to_store(rows, DT[dtype])
+    qr = orc.round_to_store(queries, DT[dtype])
+    stats = parity.check_retrieve(orc, st, qr, qtab[stage], k1, k2, lam, gpu)
+    assert gpu["cand_ids"][0, 0] == 7 and gpu["cand_ids"][0, 1] == N // 2        # tie -> lower id first
+    assert abs(gpu["cand_sims"][0, 0] - 1.0) < 1e-6
+    assert stats["boundary_swaps"] == 0 and stats["final_swaps"] == 0
+    # the same call again gives bit-identical outputs
+    again = parity.gpu_retrieve(bank, torch, queries, stage, k1, k2, lam)
+    for k in gpu:
+        assert np.array_equal(gpu[k].view(np.uint32), again[k].view(np.uint32)), k
+    assert bank.counters() == (0, 0)
+    bank.close()
+
+
+def test_edge_cases(orc):
+    rng = np.random.default_rng(101)
+    rows = _unit(rng, 10, 64)
+    q = _unit(rng, 3, 64)
+    bank = B.MemoryBank(64, "f16", 300, max_B=8, max_k1=64)
+    # empty bank: everything padded
+    out = parity.gpu_retrieve(bank, torch, q, 0, 16, 4, 0.5)
+    assert np.all(out["ids"] == -1) and np.all(np.isneginf(out["scores"])) and np.all(out["cand_ids"] == -1)
+    # one entry: pool of one, z-scores are 0
+    bank.append(_dev(rows[:1]))
+    out = parity.gpu_retrieve(bank, torch, q, 0, 16, 4, 0.5)
+    assert out["ids"][:, 0].tolist() == [0, 0, 0] and np.all(out["ids"][:, 1:] == -1) and np.all(out["scores"][:, 0] == 0)
+    # k1 > N and k2 == k1: whole bank comes back
+    bank.append(_dev(rows[1:]))
+    out = parity.gpu_retrieve(bank, torch, q, 1, 16, 16, 0.5)
+    st, qr = orc.round_to_store(rows, 2), orc.round_to_store(q, 2)
+    parity.check_retrieve(orc, st, qr, np.zeros(10, np.float32), 16, 16, 0.5, out)
+    assert sorted(out["ids"][0][:10].tolist()) == list(range(10))
+    # B = 0 is a no-op, bad arguments are rejected
+    empty = torch.empty((0, 64), device="cuda:0")
+    bank.retrieve(empty, 0, 4, 2, 0.5)
+    qd = _dev(q)
+    for kw in (dict(stage=2), dict(k1=0), dict(k2=0), dict(k1=4, k2=5), dict(k1=65), dict(lam=1.5), dict(lam=float("nan"))):
+        a = dict(stage=0, k1=8, k2=2, lam=0.5)
+        a.update(kw)
+        with pytest.raises(B.MemError) as e:
+            bank.retrieve(qd, a["stage"], a["k1"], a["k2"], a["lam"])
+        assert e.value.status == B.MEM_EINVAL
+    with pytest.raises(B.MemError):
+        bank.retrieve(_dev(_unit(rng, 9, 64)), 0, 8, 2, 0.5)         # B > max_B
+    with pytest.raises(B.MemError):
+        bank.update_q(torch.zeros(1, dtype=torch.int32, device="cuda:0"), 0, torch.zeros(1, device="cuda:0"), 0.0)
+    bank.close()
+
+
+# ----------------------------------------------------------------------------- value update
+
+def _check_update(orc, bank, stage, table, ids, rewards, alpha):
+    bank.update_q(_dev(ids), stage, _dev(rewards), alpha)
+    got = bank.read_q(stage).cpu().numpy()
+    w32, skipped = orc.update_q32(table, ids, rewards, alpha)
+    w64, _ = orc.update_q64(table, ids, rewards, alpha)
+    assert np.array_equal(got.view(np.uint32), w32.view(np.uint32))
+    assert np.max(np.abs(got.astype(np.float64) - w64)) <= 1e-6
+    return got, skipped
+
+
+def test_update_q_duplicates_order_and_untouched_entries(orc):
+    rng = np.random.default_rng(102)
+    N = 5000
+    rows = _unit(rng, N, 64)
+    qtab = rng.uniform(-1, 1, (2, N)).astype(np.float32)
+    bank = _make_bank("bf16", rows, qtab, max_B=8, max_k1=16)
+    tables = [qtab[0].copy(), qtab[1].copy()]
+    skipped_total = 0
+    # (a) few ids, (b) heavy duplication incl. a long run, (c) out-of-range ids, (d) more than one launch chunk
+    batches = [
+        (0, np.array([3, 4, 3, 3], np.int32), np.array([1, 0, 0, 1], np.float32), 0.1),
+        (1, np.concatenate([np.full(3000, 17), rng.integers(0, 50, 4000)]).astype(np.int32), None, 0.05),
+        (0, np.array([-1, 5, N, 5, 2**31 - 1, 6, -2**31], np.int32), None, 0.5),
+        (1, rng.integers(0, N, 20000).astype(np.int32), None, 0.3),
+        (0, rng.permutation(N)[:4097].astype(np.int32), None, 1.0),
+    ]
+    for stage, ids, rewards, alpha in batches:
+        if rewards is None:
+            rewards = rng.uniform(-1, 1, ids.size).astype(np.float32)
+        perm = rng.permutation(ids.size)
+        ids, rewards = ids[perm], rewards[perm]
+        other = bank.read_q(1 - stage).cpu().numpy()
+        tables[stage], sk = _check_update(orc, bank, stage, tables[stage], ids, rewards, alpha)
+        skipped_total += sk
+        assert np.array_equal(bank.read_q(1 - stage).cpu().numpy().view(np.uint32), other.view(np.uint32))
+    assert bank.counters() == (skipped_total, 0) and skipped_total == 4
+    # alpha = 1: an id keeps the LAST reward given to it in array order
+    ids = np.array([9, 8, 9, 9, 8], np.int32)
+    r = np.array([0.1, 0.2, 0.3, 0.4, 0.5], np.float32)
+    bank.update_q(_dev(ids), 0, _dev(r), 1.0)
+    got = bank.read_q(0).cpu().numpy()
+    assert got[9] == np.float32(0.4) and got[8] == np.float32(0.5)
+    bank.update_q(_dev(ids[:0]), 0, _dev(r[:0]), 0.5)          # M = 0
+    bank.close()
+
+
+def test_update_q_zipf_batch(orc):
+    """Heavily duplicated ids (Zipf s=1.1 through a fixed bijection), rewards U[0,1], step 0.05."""
+    w = synth.scaled(synth.LARGE, N=1 << 18, d=64)
+    rng = np.random.default_rng(103)
+    bank = _make_bank("bf16", _unit(rng, 4096, 64), capacity=w.N, max_B=8, max_k1=16)
+    # the Q tables cover the whole capacity only once the bank holds that many entries
+    bank.append(_dev(_unit(rng, w.N - 4096, 64)))
+    ids, rewards = synth.zipf_update(w, M=16384)
+    top = np.bincount(ids).max()
+    assert top > 1000                                           # one id really does dominate
+    table = np.zeros(w.N, np.float32)
+    got, _ = _check_update(orc, bank, 1, table, ids, rewards, 0.05)
+    assert np.count_nonzero(got) == np.unique(ids).size
+    bank.close()
+
+
+# ----------------------------------------------------------------------------- the named workloads
+
+def test_tiny_workload(orc):
+    w = synth.TINY
+    rows, q, qtab = synth.bank(w), synth.queries(w), synth.q_tables(w)
+    bank = _make_bank(w.dtype, rows, qtab, max_B=8, max_k1=64)
+    gpu = parity.gpu_retrieve(bank, torch, q, synth.DRAFT, w.k1, w.k2, w.lam)
+    stats = parity.check_retrieve(orc, rows, q, qtab[0], w.k1, w.k2, w.lam, gpu)
+    assert stats["boundary_swaps"] == 0 and stats["final_swaps"] == 0
+    ids = gpu["ids"][0].astype(np.int32)
+    rewards = np.array([1, 0, 1, 1], np.float32)
+    _check_update(orc, bank, synth.DRAFT, qtab[0], ids, rewards, w.alpha)
+    bank.close()
+
+
+def test_mid_workload(orc):
+    w = synth.MID
+    rows, q = synth.bank(w), synth.queries(w)
+    bank = _make_bank(w.dtype, rows, max_B=64, max_k1=64)
+    tables = [np.zeros(w.N, np.float32), np.zeros(w.N, np.float32)]
+    hits = [np.zeros(w.N, np.int64), np.zeros(w.N, np.int64)]
+    for stage, ids, rewards in synth.ema_rounds(w):
+        bank.update_q(_dev(ids), stage, _dev(rewards), w.alpha)
+        tables[stage], _ = orc.update_q32(tables[stage], ids, rewards, w.alpha)
+        hits[stage] += np.bincount(ids, minlength=w.N)
+    for stage in (0, 1):
+        got = bank.read_q(stage).cpu().numpy()
+        assert np.array_equal(got.view(np.uint32), tables[stage].view(np.uint32))
+        # E[Q] after t Bernoulli(0.3) rewards from Q_0 = 0 is 0.3 (1 - 0.9^t)  (App. A, EMA lemma)
+        assert abs(got.mean() - (0.3 * (1 - 0.9 ** hits[stage])).mean()) < 2e-3
+    recall = orc.recall(rows, q, w.k1, threads=8)
+    for stage in (0, 1):
+        for lam in (0.0, 0.5, 1.0):
+            print(f"mid stage={stage} lam={lam}", flush=True)
+            gpu = parity.gpu_retrieve(bank, torch, q, stage, w.k1, w.k2, lam)
+            stats = parity.check_retrieve(orc, rows, q, tables[stage], w.k1, w.k2, lam, gpu, ora_recall=recall)
+            assert stats["boundary_swaps"] == 0
+            if lam == 0.0:
+                assert np.array_equal(gpu["ids"], gpu["cand_ids"][:, :w.k2])
+    bank.close()
+
+
+def _sampled_check(orc, w, bank, rows_rounded, q, qtab_stage, stage, sample, lam):
+    gpu = parity.gpu_retrieve(bank, torch, q, stage, w.k1, w.k2, lam)
+    qr = orc.round_to_store(q, DT[w.dtype])
+    stats = parity.check_retrieve(orc, rows_rounded, qr, qtab_stage, w.k1, w.k2, lam, gpu, sample=sample)
+    # properties that hold for every query at any size
+    assert np.all(gpu["cand_ids"] >= 0) and np.all(np.diff(gpu["cand_sims"], axis=1) <= 0)
+    assert np.all(np.diff(gpu["scores"], axis=1) <= 0)
+    for b in range(q.shape[0]):
+        assert set(gpu["ids"][b].tolist()) <= set(gpu["cand_ids"][b].tolist())
+    return gpu, stats
+
+
+def test_clustered_workload_full_size(orc):
+    """N = 1,048,576 x 1024 bf16, B = 256, k1 = 128, k2 = 16: the launch configuration the benchmark
+    times.  The oracle checks 8 sampled queries over the full bank; near-ties are common here."""
+    w = synth.CLUSTERED
+    qtab = synth.q_tables(w)
+    bank = B.MemoryBank(w.d, w.dtype, w.N, max_B=w.B, max_k1=w.k1)
+    rounded = np.empty((w.N, w.d), np.float32)
+    for j in range(synth.n_chunks(w)):
+        c = synth.bank_chunk(w, j)
+        a = j * synth.CHUNK_ROWS
+        bank.append(_dev(c), _dev(qtab[0, a:a + len(c)]), _dev(qtab[1, a:a + len(c)]))
+        rounded[a:a + len(c)] = orc.round_to_store(c, DT[w.dtype])
+    print("clustered bank built", flush=True)
+    q = synth.queries(w)
+    sample = [0, 37, 90, 128, 129, 200, 254, 255]
+    gpu, stats = _sampled_check(orc, w, bank, rounded, q, qtab[0], 0, sample, w.lam)
+    print("clustered stats", stats, flush=True)
+    # secondary bound for 16-bit storage: similarities of the rounded vectors stay within 2e-2
+    # (relative) of the similarities of the unrounded fp32 vectors
+    for b in sample[:3]:
+        ids = gpu["cand_ids"][b][:8]
+        raw = np.stack([synth.bank_chunk(w, int(i) // synth.CHUNK_ROWS)[int(i) % synth.CHUNK_ROWS] for i in ids])
+        true = raw.astype(np.float64) @ q[b].astype(np.float64)
+        assert np.all(np.abs(gpu["cand_sims"][b][:8] - true) <= 2e-2 * np.abs(true))
+    g0 = parity.gpu_retrieve(bank, torch, q, 0, w.k1, w.k2, 0.0)
+    assert np.array_equal(g0["ids"], g0["cand_ids"][:, :w.k2])          # lambda = 0: similarity ranking
+    assert bank.counters() == (0, 0)
+    bank.close()
+
+
+def test_large_workload_reduced(orc):
+    """Shape of the large batched workload (d = 1536 bf16, B = 1024, k1 = 128, refine stage) on a
+    262,144-entry bank, 8 sampled queries against the oracle."""
+    w = synth.scaled(synth.LARGE, N=1 << 18)
+    rows = synth.bank(w)
+    qtab = synth.q_tables(w)
+    bank = _make_bank(w.dtype, rows, qtab, max_B=w.B, max_k1=w.k1)
+    rounded = orc.round_to_store(rows, DT[w.dtype])
+    q = synth.queries(w)
+    _, stats = _sampled_check(orc, w, bank, rounded, q, qtab[1], 1, [0, 255, 256, 511, 600, 767, 1000, 1023], w.lam)
+    print("large stats", stats, flush=True)
+    assert bank.counters() == (0, 0)
+    bank.close()
+
+
+def test_stream_workload_reduced(orc):
+    """Shape of the streaming workload (d = 4096 fp16, B = 128, k1 = 256, k2 = 32, lambda 0.7): the
+    bank grows by 16,384-entry chunks from 32,768; every step appends, retrieves (alternating
+    stage) and updates the B*k2 returned ids with Bernoulli(0.2) rewards."""
+    w = synth.scaled(synth.STREAM, N=1 << 17)
+    chunk, n0, steps = 16384, 32768, 4
+    bank = B.MemoryBank(w.d, w.dtype, n0 + steps * chunk, max_B=w.B, max_k1=w.k1)
+    rows = np.concatenate([synth.bank_chunk(w, j, chunk) for j in range(n0 // chunk + steps)])
+    rounded = orc.round_to_store(rows, DT[w.dtype])
+    bank.append(_dev(rows[:n0]))
+    tables = [np.zeros(n0 + steps * chunk, np.float32) for _ in range(2)]
+    n = n0
+    for t in range(steps):
+        bank.append(_dev(rows[n:n + chunk]))
+        n += chunk
+        stage = t % 2
+        q = synth.queries(w, step=t)
+        print(f"stream step {t} N={n}", flush=True)
+        gpu = parity.gpu_retrieve(bank, torch, q, stage, w.k1, w.k2, w.lam)
+        qr = orc.round_to_store(q, DT[w.dtype])
+        parity.check_retrieve(orc, rounded[:n], qr, tables[stage][:n], w.k1, w.k2, w.lam, gpu, sample=[0, 64, 127])
+        ids = gpu["ids"].reshape(-1).astype(np.int32)
+        rewards = synth.bernoulli_rewards(w, t, ids.size)
+        bank.update_q(_dev(ids), stage, _dev(rewards), w.alpha)
+        tables[stage][:n], _ = orc.update_q32(tables[stage][:n], ids, rewards, w.alpha)
+        assert np.array_equal(bank.read_q(stage).cpu().numpy().view(np.uint32), tables[stage][:n].view(np.uint32))
+    assert bank.counters() == (0, 0)
+    bank.close()
