@@ -56,8 +56,11 @@ __global__ __launch_bounds__(1024) void k_update_q(const int32_t* __restrict__ i
         float q = qstage[id];
         int j = i;
         do {
+#pragma clang fp contract(off)   // three separately rounded operations, never a fused multiply-add
             float r = __uint_as_float((uint32_t)keys[j]);
-            q = __fadd_rn(q, __fmul_rn(alpha, __fsub_rn(r, q)));
+            float diff = r - q;
+            float stepv = alpha * diff;
+            q = q + stepv;
             ++j;
         } while (j < npad && (uint32_t)(keys[j] >> 32) == id && keys[j] != ~0ull);
         qstage[id] = q;
