@@ -331,23 +331,29 @@ extern "C" int mem_retrieve(evomem_t* h, const float* queries_dev, int B, int st
     double* exact = (double*)(ws + h->w.exact);
     uint32_t* counters = (uint32_t*)(ws + h->w.counters);
 
+    std::vector<Level> levels;
+    uint32_t cnt0 = 0;      // valid rows of the sparsest pass (a prefix of its last tile may be all that exists)
+    if (h->N > 0) {
+        levels = plan_levels(h->N, k1);
+        const Level& L0 = levels[0];
+        const int64_t last = level_tile(L0, L0.ntiles - 1) * TILE_ROWS;
+        const int64_t in_last = h->N - last < TILE_ROWS ? h->N - last : TILE_ROWS;
+        cnt0 = (uint32_t)((int64_t)(L0.ntiles - 1) * TILE_ROWS + in_last);
+    }
     if (h->dtype == MEM_F32)
-        hipLaunchKernelGGL(k_prep_queries<0>, dim3(Bp), dim3(256), 0, st, queries_dev, B, Bp, h->d, h->nkb, qf, qop, invq, invq64, thr, cnt);
+        hipLaunchKernelGGL(k_prep_queries<0>, dim3(Bp), dim3(256), 0, st, queries_dev, B, Bp, h->d, h->nkb, qf, qop, invq, invq64, thr, cnt, cnt0);
     else if (h->dtype == MEM_BF16)
-        hipLaunchKernelGGL(k_prep_queries<1>, dim3(Bp), dim3(256), 0, st, queries_dev, B, Bp, h->d, h->nkb, qf, qop, invq, invq64, thr, cnt);
+        hipLaunchKernelGGL(k_prep_queries<1>, dim3(Bp), dim3(256), 0, st, queries_dev, B, Bp, h->d, h->nkb, qf, qop, invq, invq64, thr, cnt, cnt0);
     else
-        hipLaunchKernelGGL(k_prep_queries<2>, dim3(Bp), dim3(256), 0, st, queries_dev, B, Bp, h->d, h->nkb, qf, qop, invq, invq64, thr, cnt);
+        hipLaunchKernelGGL(k_prep_queries<2>, dim3(Bp), dim3(256), 0, st, queries_dev, B, Bp, h->d, h->nkb, qf, qop, invq, invq64, thr, cnt, cnt0);
     LAUNCHCHK();
 
-    // guard band of the selected list and rounding margin of the scan's fp32 similarities
-    int keep = k1 + (k1 / 2 > 32 ? k1 / 2 : 32);
-    if (keep > KEEP_MAX) keep = KEEP_MAX;
+    // rounding margin of the scan's fp32 similarities
     float eps = (float)(h->nkb * KB) * 5.97e-8f + 1e-6f;
     if (h->dtype == MEM_F32 && !gemv) eps += 2e-5f;      // bf16 hi/lo split of fp32 values
     const float margin = 2.f * eps;
 
     if (h->N > 0) {
-        std::vector<Level> levels = plan_levels(h->N, k1);
         for (const Level& L : levels) {
             const bool prof = h->prof_on && h->prof_n < MAX_PROFILE;
             if (prof) HIPCHK(hipEventRecord(h->ev[2 * h->prof_n], st));
@@ -364,10 +370,10 @@ extern "C" int mem_retrieve(evomem_t* h, const float* queries_dev, int B, int st
                 int64_t rows = (int64_t)L.ntiles * TILE_ROWS;
                 h->prof_rows[h->prof_n++] = rows;
             }
-            hipLaunchKernelGGL(k_select, dim3(B), dim3(1024), 0, st, surv, cnt, thr, (const float*)invq, counters, k1, keep, margin);
+            hipLaunchKernelGGL(k_select, dim3(B), dim3(1024), 0, st, surv, cnt, thr, (const float*)invq, counters, k1, margin);
             LAUNCHCHK();
         }
-        dim3 rgrid((unsigned)((keep + 3) / 4), (unsigned)B);
+        dim3 rgrid((unsigned)(KEEP_MAX / 4), (unsigned)B);
         if (h->dtype == MEM_F32)
             hipLaunchKernelGGL(k_rescore<0>, rgrid, dim3(256), 0, st, (const void*)h->store, (const float*)qf, (const double*)invq64, (const uint64_t*)surv, (const uint32_t*)cnt, exact, h->nkb);
         else if (h->dtype == MEM_BF16)

@@ -113,13 +113,15 @@ __global__ __launch_bounds__(256) void k_read_rows32(const float* __restrict__ s
 //   qop = [kb][Bpad][64 elements], 16-byte chunks swizzled like the bank rows      (16-bit stores)
 //   qop = [kb][half h][Bpad][32 hi | 32 lo bf16], same swizzle                      (fp32 stores:
 //         the query is split as hi + lo in bf16 so that the scan can use bf16 MFMA)
-// plus its inverse norm (fp32 and fp64).  Also resets the per-query survivor count and threshold.
+// plus its inverse norm (fp32 and fp64).  Also resets the per-query threshold and presets the
+// survivor count to the number of rows of the sparsest scan pass, which keeps every row.
 // One workgroup per padded query slot; slots >= B become all-zero queries that never pass a filter.
 template <int DT>
 __global__ __launch_bounds__(256) void k_prep_queries(const float* __restrict__ q, int B, int Bpad, int d, int nkb,
                                                       float* __restrict__ qf, uint16_t* __restrict__ qop,
                                                       float* __restrict__ invq, double* __restrict__ invq64,
-                                                      float* __restrict__ thr, uint32_t* __restrict__ cnt) {
+                                                      float* __restrict__ thr, uint32_t* __restrict__ cnt,
+                                                      uint32_t cnt0) {
     int b = blockIdx.x, tid = threadIdx.x;
     int dpad = nkb * KB;
     __shared__ double red[256];
@@ -174,7 +176,7 @@ __global__ __launch_bounds__(256) void k_prep_queries(const float* __restrict__ 
         invq64[b] = inv;
         invq[b] = (float)inv;
         thr[b] = live ? -INFINITY : INFINITY;
-        cnt[b] = 0;
+        cnt[b] = live ? cnt0 : 0u;     // rows the sparsest pass will write without counting
     }
 }
 

@@ -84,7 +84,9 @@ __global__ __launch_bounds__(256) void k_scan_gemv16(const uint16_t* __restrict_
         for (int b = 0; b < NB; ++b) {
             if (b >= B) break;
             float v = acc[i][b] * inve;
-            if (v >= thr[b]) append_survivor(v, invq[b], (int32_t)id, cnt + b, surv + (int64_t)b * SURV_CAP);
+            if (L.rho == 0)      // sparsest pass keeps every row at its own position, no counter
+                surv[(int64_t)b * SURV_CAP + (int64_t)blockIdx.x * TILE_ROWS + (id - t * TILE_ROWS)] = pack_key(v * invq[b], (int32_t)id);
+            else if (v >= thr[b]) append_survivor(v, invq[b], (int32_t)id, cnt + b, surv + (int64_t)b * SURV_CAP);
         }
     }
 }
@@ -142,7 +144,9 @@ __global__ __launch_bounds__(256) void k_scan_gemv32(const float* __restrict__ s
         for (int b = 0; b < NB; ++b) {
             if (b >= B) break;
             float v = acc[i][b] * inve;
-            if (v >= thr[b]) append_survivor(v, invq[b], (int32_t)id, cnt + b, surv + (int64_t)b * SURV_CAP);
+            if (L.rho == 0)      // sparsest pass keeps every row at its own position, no counter
+                surv[(int64_t)b * SURV_CAP + (int64_t)blockIdx.x * TILE_ROWS + (id - t * TILE_ROWS)] = pack_key(v * invq[b], (int32_t)id);
+            else if (v >= thr[b]) append_survivor(v, invq[b], (int32_t)id, cnt + b, surv + (int64_t)b * SURV_CAP);
         }
     }
 }

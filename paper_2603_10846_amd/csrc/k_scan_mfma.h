@@ -42,7 +42,14 @@ __device__ __forceinline__ uint32_t pack_bf16x2_hi(float a, float b, float& ra, 
 
 constexpr int STAGE_BANK_BYTES = TILE_ROWS * 128;
 
-template <int QT> constexpr int scan_mfma_lds_bytes() { return 2 * (STAGE_BANK_BYTES + QT * 128) + QT * 4; }
+// LDS: two stages (bank tile + query tile), then per-query threshold, inverse norm, survivor count
+// and list base, then one counter.  After the k-loop the stage area is reused as the workgroup's
+// survivor list (8-byte key + 4-byte query index per entry).
+template <int QT> constexpr int scan_mfma_lds_bytes() { return 2 * (STAGE_BANK_BYTES + QT * 128) + QT * 16 + 16; }
+template <int QT> constexpr int scan_mfma_list_cap() {
+    int c = 2 * (STAGE_BANK_BYTES + QT * 128) / 12 / 256 * 256;
+    return c > 8192 ? 8192 : c;
+}
 
 // DT: 0 fp32 store (bf16 split), 1 bf16, 2 f16.  Wave grid WQ x WR, each wave MQ x MR blocks of 32x32.
 template <int DT, int MQ, int WQ, int MR, int WR>
@@ -72,8 +79,13 @@ __global__ __launch_bounds__(256) void k_scan_mfma(const void* __restrict__ stor
     constexpr int STAGE_BYTES = STAGE_BANK_BYTES + QT * 128;
     auto sbank = [&](int s) { return smem + s * STAGE_BYTES; };
     auto sq = [&](int s) { return smem + s * STAGE_BYTES + STAGE_BANK_BYTES; };
-    float* thr_s = reinterpret_cast<float*>(smem + 2 * (STAGE_BANK_BYTES + QT * 128));
-    for (int i = tid; i < QT; i += 256) thr_s[i] = thr[q0 + i];
+    float* thr_s = reinterpret_cast<float*>(smem + 2 * STAGE_BYTES);
+    float* invq_s = thr_s + QT;
+    uint32_t* cnt_s = reinterpret_cast<uint32_t*>(invq_s + QT);
+    uint32_t* base_s = cnt_s + QT;
+    uint32_t* total_s = base_s + QT;
+    for (int i = tid; i < QT; i += 256) { thr_s[i] = thr[q0 + i]; invq_s[i] = invq[q0 + i]; cnt_s[i] = 0; }
+    if (tid == 0) *total_s = 0;
 
     f32x16_t acc[MQ][MR];
 #pragma unroll
@@ -181,8 +193,34 @@ __global__ __launch_bounds__(256) void k_scan_mfma(const void* __restrict__ stor
         __syncthreads();
     }
 
-    // ---- epilogue: filter against the per-query thresholds ----
+    // ---- epilogue ----
     const int half = lane >> 5, l32 = lane & 31;
+    if (L.rho == 0) {
+        // Sparsest pass: no threshold yet, every row is kept.  Slot = position of the row in this
+        // pass, so no counter is needed (the count was preset to the pass's number of valid rows).
+#pragma unroll
+        for (int b = 0; b < MR; ++b) {
+            const int rt = (wr * MR + b) * 32 + l32;
+            const int64_t id = t * TILE_ROWS + rt;
+            if (id >= N) continue;
+            const float inve = invnorm[id];
+            const int64_t pos = (int64_t)j * TILE_ROWS + rt;
+#pragma unroll
+            for (int a = 0; a < MQ; ++a)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int ql = (wq * MQ + a) * 32 + 4 * half + 8 * (r >> 2) + (r & 3);
+                    surv[(int64_t)(q0 + ql) * SURV_CAP + pos] = pack_key(acc[a][b][r] * inve * invq_s[ql], (int32_t)id);
+                }
+        }
+        return;
+    }
+    // Filter against the per-query thresholds.  Survivors (rare) go to a workgroup list in LDS first,
+    // so that the global slot counters are bumped once per (workgroup, query) and all at the same
+    // time, instead of one dependent device-wide atomic per survivor.
+    constexpr int LCAP = scan_mfma_list_cap<QT>();
+    uint64_t* lkey = reinterpret_cast<uint64_t*>(smem);
+    uint32_t* lq = reinterpret_cast<uint32_t*>(smem + LCAP * 8);
 #pragma unroll
     for (int b = 0; b < MR; ++b) {
         const int64_t id = t * TILE_ROWS + (wr * MR + b) * 32 + l32;
@@ -200,14 +238,35 @@ __global__ __launch_bounds__(256) void k_scan_mfma(const void* __restrict__ stor
             }
             if (!valid) m = 0;
             if (m) {
+                uint32_t slot = atomicAdd(total_s, (uint32_t)__popc(m));
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
                     if (m & (1u << r)) {
-                        int q = q0 + qb + 8 * (r >> 2) + (r & 3);
-                        append_survivor(v[r], invq[q], (int32_t)id, cnt + q, surv + (int64_t)q * SURV_CAP);
+                        const int ql = qb + 8 * (r >> 2) + (r & 3);
+                        const uint64_t key = pack_key(v[r] * invq_s[ql], (int32_t)id);
+                        if (slot < (uint32_t)LCAP) { lkey[slot] = key; lq[slot] = (uint32_t)ql; }
+                        else {   // list full (a very loose threshold): fall back to the direct path
+                            uint32_t pos = atomicAdd(cnt + q0 + ql, 1u);
+                            if (pos < (uint32_t)SURV_CAP) surv[(int64_t)(q0 + ql) * SURV_CAP + pos] = key;
+                        }
+                        ++slot;
                     }
             }
         }
+    }
+    __syncthreads();
+    const uint32_t total = *total_s < (uint32_t)LCAP ? *total_s : (uint32_t)LCAP;
+    for (uint32_t e = tid; e < total; e += 256) {
+        uint32_t ql = lq[e];
+        lq[e] = ql | (atomicAdd(cnt_s + ql, 1u) << 16);        // rank within this workgroup's entries of ql
+    }
+    __syncthreads();
+    for (int i = tid; i < QT; i += 256) { uint32_t c = cnt_s[i]; base_s[i] = c ? atomicAdd(cnt + q0 + i, c) : 0u; }
+    __syncthreads();
+    for (uint32_t e = tid; e < total; e += 256) {
+        uint32_t ql = lq[e] & 0xffffu, rank = lq[e] >> 16;
+        uint32_t pos = base_s[ql] + rank;
+        if (pos < (uint32_t)SURV_CAP) surv[(int64_t)(q0 + ql) * SURV_CAP + pos] = lkey[e];
     }
 }
 

@@ -21,33 +21,92 @@ __device__ __forceinline__ void bitonic_desc(T* a, int n, int tid, int nthreads,
         }
 }
 
-// After a scan pass: order the query's survivors by (similarity desc, id asc), keep the best `keep`
-// (k1 plus a guard band) at the head of its list as the seed of the next pass, and set the next
-// pass's threshold to the k1-th best similarity minus `margin` (a bound on the scan's rounding
-// error, so that no true member of the pool can be filtered out), pre-divided by the query's
-// inverse norm because the scan compares before applying it.  One workgroup per query.
+// After a scan pass, for one query: find the k1-th best survivor key (similarity desc, id asc) by
+// an MSB-first radix select over the packed 64-bit keys, set the next pass's threshold to that
+// similarity minus `margin` (a bound on the scan's fp32 rounding error, so that no true member of
+// the pool can be filtered out; pre-divided by the query's inverse norm because the scan compares
+// before applying it), and compact every key whose similarity reaches that threshold to the head of
+// the list: these seed the next pass and, after the last pass, are the candidates that get re-scored
+// in fp64.  Nothing is sorted here -- slot order is irrelevant to every consumer.
+// Keys live in registers (8 per lane, 1024 lanes); each radix pass builds per-wavefront digit
+// histograms in LDS, sums them, and one wavefront picks the digit by a suffix scan.
 __global__ __launch_bounds__(1024) void k_select(uint64_t* __restrict__ surv, uint32_t* __restrict__ cnt,
                                                  float* __restrict__ thr, const float* __restrict__ invq,
-                                                 uint32_t* __restrict__ counters, int k1, int keep, float margin) {
-    __shared__ uint64_t keys[SURV_CAP];
-    const int b = blockIdx.x, tid = threadIdx.x;
+                                                 uint32_t* __restrict__ counters, int k1, float margin) {
+    __shared__ uint32_t hist[16][256];
+    __shared__ uint32_t tot[256];
+    __shared__ uint64_t pivot_s;
+    __shared__ uint32_t sel_digit, sel_need, sel_single, band_s, nout_s;
+    const int b = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     uint64_t* list = surv + (int64_t)b * SURV_CAP;
-    uint32_t raw = cnt[b];
-    int n = raw > (uint32_t)SURV_CAP ? SURV_CAP : (int)raw;
+    const uint32_t raw = cnt[b];
+    const int n = raw > (uint32_t)SURV_CAP ? SURV_CAP : (int)raw;
     if (raw > (uint32_t)SURV_CAP && tid == 0) atomicAdd(counters + 1, 1u);
-    int npad = 2;
-    while (npad < n) npad <<= 1;
-    for (int i = tid; i < npad; i += 1024) keys[i] = i < n ? list[i] : 0ull;
-    __syncthreads();
-    bitonic_desc(keys, npad, tid, 1024, [](uint64_t x, uint64_t y) { return x < y; });
-    int kk = n < keep ? n : keep;
-    for (int i = tid; i < kk; i += 1024) list[i] = keys[i];
-    if (tid == 0) {
-        cnt[b] = (uint32_t)kk;
-        float t = -INFINITY;
-        if (n >= k1) t = (key_sim(keys[k1 - 1]) - margin) / invq[b];
-        thr[b] = t;
+    if (n < k1) {                       // fewer rows than the pool size: keep them all, no threshold
+        if (tid == 0) { cnt[b] = (uint32_t)n; thr[b] = -INFINITY; }
+        return;
     }
+    uint64_t key[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { int idx = i * 1024 + tid; key[i] = idx < n ? list[idx] : 0ull; }   // 0 = empty
+    if (tid == 0) { band_s = 0; nout_s = 0; }
+    uint64_t prefix = 0, pivot = 0;
+    uint32_t need = (uint32_t)k1;
+    for (int pass = 0; pass < 8; ++pass) {
+        const int shift = 56 - 8 * pass;
+        for (int i = tid; i < 16 * 256; i += 1024) (&hist[0][0])[i] = 0;
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            if (key[i] != 0 && (pass == 0 || (key[i] >> (shift + 8)) == (prefix >> (shift + 8))))
+                atomicAdd(&hist[wave][(uint32_t)(key[i] >> shift) & 255u], 1u);
+        __syncthreads();
+        if (tid < 256) {
+            uint32_t s = 0;
+#pragma unroll
+            for (int w = 0; w < 16; ++w) s += hist[w][tid];
+            tot[tid] = s;
+        }
+        __syncthreads();
+        if (wave == 0) {                // lane l owns digits 4l .. 4l+3; larger digit = better key
+            uint32_t c[4] = {tot[4 * lane], tot[4 * lane + 1], tot[4 * lane + 2], tot[4 * lane + 3]};
+            uint32_t local = c[0] + c[1] + c[2] + c[3], incl = local;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) { uint32_t t = __shfl_down(incl, o, 64); if (lane + o < 64) incl += t; }
+            uint32_t run = incl - local;            // keys with a digit in a higher lane
+#pragma unroll
+            for (int k = 3; k >= 0; --k) {
+                if (run < need && run + c[k] >= need) { sel_digit = 4 * lane + k; sel_need = need - run; sel_single = c[k] == 1; }
+                run += c[k];
+            }
+        }
+        __syncthreads();
+        prefix |= (uint64_t)sel_digit << shift;
+        need = sel_need;
+        if (sel_single || pass == 7) {              // one key left under this prefix: it is the k1-th best
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                if (key[i] != 0 && (key[i] >> shift) == (prefix >> shift)) pivot_s = key[i];
+            __syncthreads();
+            pivot = pivot_s;
+            break;
+        }
+    }
+    const float tau = key_sim(pivot) - margin;
+    uint64_t cutkey = (uint64_t)f2ord(tau) << 32;   // every key with similarity >= tau compares >= cutkey
+    uint32_t mine = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) mine += key[i] != 0 && key[i] >= cutkey;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mine += __shfl_xor(mine, o, 64);
+    if (lane == 0 && mine) atomicAdd(&band_s, mine);
+    __syncthreads();
+    if (band_s > (uint32_t)KEEP_MAX) cutkey = pivot;    // band too crowded: keep exactly the k1 best
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+        if (key[i] != 0 && key[i] >= cutkey) list[atomicAdd(&nout_s, 1u)] = key[i];
+    __syncthreads();
+    if (tid == 0) { cnt[b] = nout_s; thr[b] = tau / invq[b]; }
 }
 
 // Exact similarities of the selected candidates: one wavefront per (query, candidate) re-reads the
