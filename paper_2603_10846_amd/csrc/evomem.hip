@@ -39,7 +39,7 @@ Workspace carve(int d, int dtype, int max_B) {
     auto take = [&](size_t bytes) { size_t at = o; o = (size_t)round_up((int64_t)(o + bytes), 256); return at; };
     w.counters = take(256);
     w.qf = take((size_t)Bp * dpad * 4);
-    w.qop = take((size_t)Bp * dpad * (dtype == MEM_F32 ? 4 : 2));
+    w.qop = take((size_t)Bp * (dpad + KB) * (dtype == MEM_F32 ? 4 : 2));   // + one all-zero k-block
     w.invq = take((size_t)Bp * 4);
     w.invq64 = take((size_t)Bp * 8);
     w.thr = take((size_t)Bp * 4);
@@ -250,13 +250,21 @@ int launch_mfma(evomem* h, hipStream_t st, int Bp, const Level& L) {
     constexpr int QT = 32 * MQ * WQ;
     constexpr int lds = scan_mfma_lds_bytes<QT>();
     auto kern = k_scan_mfma<DT, MQ, WQ, MR, WR>;
-    static bool attr_done[16] = {};
-    if (!attr_done[h->device & 15]) {
+    static int resident[16] = {};          // workgroups of this kernel the whole device holds at once
+    if (!resident[h->device & 15]) {
         HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds));
-        attr_done[h->device & 15] = true;
+        int per_cu = 0, cus = 0;
+        HIPCHK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(kern), 256, lds));
+        HIPCHK(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, h->device));
+        if (per_cu < 1 || cus < 8) return MEM_EHIP;
+        resident[h->device & 15] = per_cu * cus;
     }
+    // persistent launch: per XCD, `groups` tile walkers for each of the nqt query tiles
     const int nqt = Bp / QT;
-    dim3 grid((unsigned)(8 * ((L.ntiles + 7) / 8) * nqt)), block(256);
+    int groups = resident[h->device & 15] / 8 / nqt;
+    if (groups < 1) groups = 1;
+    if (groups > (L.ntiles + 7) / 8) groups = (L.ntiles + 7) / 8;
+    dim3 grid((unsigned)(8 * nqt * groups)), block(256);
     unsigned char* ws = h->ws;
     hipLaunchKernelGGL(kern, grid, block, lds, st, (const void*)h->store, (const float*)h->invnorm,
                        (const uint16_t*)(ws + h->w.qop), (const float*)(ws + h->w.invq), (const float*)(ws + h->w.thr),

@@ -110,7 +110,8 @@ __global__ __launch_bounds__(256) void k_read_rows32(const float* __restrict__ s
 // Query preparation (Sec. 3.2, the query side of dense retrieval): round each query to the store's
 // element type, keep it widened (fp32, row-major, zero-padded to the k-block multiple) for the
 // GEMV scan and the fp64 re-score, and in the operand layout of the MFMA scan
-//   qop = [kb][Bpad][64 elements], 16-byte chunks swizzled like the bank rows      (16-bit stores)
+//   qop = [kb][Bpad][64 elements], 16-byte chunks swizzled like the bank rows, plus one all-zero
+//         k-block at kb = nkb                                                        (16-bit stores)
 //   qop = [kb][half h][Bpad][32 hi | 32 lo bf16], same swizzle                      (fp32 stores:
 //         the query is split as hi + lo in bf16 so that the scan can use bf16 MFMA)
 // plus its inverse norm (fp32 and fp64).  Also resets the per-query threshold and presets the
@@ -167,6 +168,9 @@ __global__ __launch_bounds__(256) void k_prep_queries(const float* __restrict__ 
         *reinterpret_cast<float4*>(o) = make_float4(v[0], v[1], v[2], v[3]);
         *reinterpret_cast<float4*>(o + 4) = make_float4(v[4], v[5], v[6], v[7]);
     }
+    // one all-zero k-block behind the last one: the MFMA scan pairs it with a repeated bank block
+    // when it pads an odd number of k-steps to an even one
+    if (DT != 0 && tid < 8) *reinterpret_cast<uint4*>(qop + ((int64_t)nkb * Bpad + b) * KB + tid * 8) = make_uint4(0, 0, 0, 0);
     red[tid] = ssq;
     __syncthreads();
     for (int s = 128; s > 0; s >>= 1) { if (tid < s) red[tid] += red[tid + s]; __syncthreads(); }

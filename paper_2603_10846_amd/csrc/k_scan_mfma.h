@@ -1,11 +1,14 @@
 // Similarity scan for query batches large enough to be a dense contraction (Sec. 3.2, dense
 // recall): scores[q][n] = <query q, bank row n> on the matrix cores, never written to memory.
 //
-// A workgroup of 4 wavefronts owns one 256-row bank tile and QT queries.  Per k-block the bank
-// tile's 32 KB block (already in LDS operand order in HBM, see layout.h) and the queries' block are
-// staged in LDS, double buffered, and consumed by v_mfma_f32_32x32x16 (bf16 or f16 operands, fp32
-// accumulation).  Queries are the rows of the accumulator tile and bank rows its columns, so a lane
-// holds one bank row per 32x32 block and the per-row inverse norm is a per-lane constant.
+// Persistent workgroups of 4 wavefronts; each owns QT queries and walks over 256-row bank tiles.
+// Per k-block the bank tile's 32 KB block (already in LDS operand order in HBM, see layout.h) and
+// the queries' block are staged in LDS (two stages) and consumed by v_mfma_f32_32x32x16 (bf16 or
+// f16 operands, fp32 accumulation).  Global loads run two k-blocks ahead of the MFMAs through two
+// register sets, and the (tile, k-block) sequence is flattened, so the loads of the next tile are
+// already in flight while a tile's epilogue runs.  Queries are the rows of the accumulator tile and
+// bank rows its columns: a lane holds one bank row per 32x32 block and the row's inverse norm is a
+// per-lane constant in the epilogue.
 //
 // fp32 stores: each value is split on the fly into bf16 hi + bf16 lo and the product is
 // hi*hi + hi*lo + lo*hi (three MFMAs, relative error of a product about 2^-16); this only has to
@@ -14,6 +17,8 @@
 // Epilogue: score * invnorm[row] is compared with the query's threshold (pre-divided by the
 // query's inverse norm); the rare survivors are appended to the query's list.
 #pragma once
+#include <type_traits>
+
 #include "k_scan_gemv.h"
 #include "layout.h"
 
@@ -41,17 +46,16 @@ __device__ __forceinline__ uint32_t pack_bf16x2_hi(float a, float b, float& ra, 
 }
 
 constexpr int STAGE_BANK_BYTES = TILE_ROWS * 128;
+constexpr int SCAN_LIST_CAP = 2048;     // survivor entries a workgroup can stage per tile
 
-// LDS: two stages (bank tile + query tile), then per-query threshold, inverse norm, survivor count
-// and list base, then one counter.  After the k-loop the stage area is reused as the workgroup's
-// survivor list (8-byte key + 4-byte query index per entry).
-template <int QT> constexpr int scan_mfma_lds_bytes() { return 2 * (STAGE_BANK_BYTES + QT * 128) + QT * 16 + 16; }
-template <int QT> constexpr int scan_mfma_list_cap() {
-    int c = 2 * (STAGE_BANK_BYTES + QT * 128) / 12 / 256 * 256;
-    return c > 8192 ? 8192 : c;
+// LDS: two stages (bank tile + query tile); per-query threshold, inverse norm, survivor count and
+// list base; the workgroup's survivor list (8-byte key + 4-byte query index per entry); a counter.
+template <int QT> constexpr int scan_mfma_lds_bytes() {
+    return 2 * (STAGE_BANK_BYTES + QT * 128) + QT * 16 + SCAN_LIST_CAP * 12 + 16;
 }
 
 // DT: 0 fp32 store (bf16 split), 1 bf16, 2 f16.  Wave grid WQ x WR, each wave MQ x MR blocks of 32x32.
+// gridDim.x is a multiple of 8 * (Bp / QT).
 template <int DT, int MQ, int WQ, int MR, int WR>
 __global__ __launch_bounds__(256) void k_scan_mfma(const void* __restrict__ store_, const float* __restrict__ invnorm,
                                                    const uint16_t* __restrict__ qop, const float* __restrict__ invq,
@@ -61,61 +65,76 @@ __global__ __launch_bounds__(256) void k_scan_mfma(const void* __restrict__ stor
     static_assert(WQ * WR == 4 && MR * WR == 8, "4 waves, 256 bank rows per workgroup");
     constexpr int QT = 32 * MQ * WQ;
     constexpr int QCH = QT / 32;                       // 16-byte query chunks per lane per stage
+    constexpr int STAGE_BYTES = STAGE_BANK_BYTES + QT * 128;
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wq = wave / WR, wr = wave % WR;
+    const int half = lane >> 5, l32 = lane & 31;
 
-    // blockIdx -> (bank tile, query tile): workgroups that share a bank tile get consecutive slots
-    // of one XCD (blocks are dealt to the 8 XCDs round-robin), so the tile is fetched from HBM once
-    // and the other query tiles hit that XCD's L2.
+    // Workgroup -> (query tile, sequence of bank tiles).  Blocks are dealt to the 8 XCDs round-robin;
+    // the nqt workgroups that share a bank tile are neighbours on one XCD and walk the tiles in the
+    // same order, so a tile is fetched from HBM once and the other query tiles hit that XCD's L2.
     const int nqt = Bp / QT;
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    const int qt = slot % nqt;
-    const int j = (slot / nqt) * 8 + xcd;
-    if (j >= L.ntiles) return;
-    const int64_t t = level_tile(L, j);
+    const int qt = slot % nqt, group = slot / nqt;
+    const int groups = (gridDim.x >> 3) / nqt;         // tile walkers per XCD
     const int q0 = qt * QT;
+    // tiles of this workgroup: j = (group + i * groups) * 8 + xcd < L.ntiles
+    const int first_j = group * 8 + xcd, stride_j = groups * 8;
+    if (first_j >= L.ntiles) return;
+    const int my_tiles = (L.ntiles - first_j + stride_j - 1) / stride_j;
 
-    constexpr int STAGE_BYTES = STAGE_BANK_BYTES + QT * 128;
-    auto sbank = [&](int s) { return smem + s * STAGE_BYTES; };
-    auto sq = [&](int s) { return smem + s * STAGE_BYTES + STAGE_BANK_BYTES; };
+    auto sbank = [&](int s) __attribute__((always_inline)) { return smem + s * STAGE_BYTES; };
+    auto sq = [&](int s) __attribute__((always_inline)) { return smem + s * STAGE_BYTES + STAGE_BANK_BYTES; };
     float* thr_s = reinterpret_cast<float*>(smem + 2 * STAGE_BYTES);
     float* invq_s = thr_s + QT;
     uint32_t* cnt_s = reinterpret_cast<uint32_t*>(invq_s + QT);
     uint32_t* base_s = cnt_s + QT;
-    uint32_t* total_s = base_s + QT;
+    uint64_t* lkey = reinterpret_cast<uint64_t*>(base_s + QT);
+    uint32_t* lq = reinterpret_cast<uint32_t*>(lkey + SCAN_LIST_CAP);
+    uint32_t* total_s = lq + SCAN_LIST_CAP;
     for (int i = tid; i < QT; i += 256) { thr_s[i] = thr[q0 + i]; invq_s[i] = invq[q0 + i]; cnt_s[i] = 0; }
     if (tid == 0) *total_s = 0;
 
+    // Accumulators: never zeroed explicitly -- the first MFMA of a tile takes a zero C operand.
+    // (An explicit re-zeroing inside the tile loop makes the compiler keep two copies of them.)
     f32x16_t acc[MQ][MR];
-#pragma unroll
-    for (int a = 0; a < MQ; ++a)
-#pragma unroll
-        for (int b = 0; b < MR; ++b)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
-    const int nsteps = DT == 0 ? nkb * 2 : nkb;
-    u32x4_t gb[8], gq[QCH];
+    // Steps per tile, made even so that the two register sets / LDS stages are in the same phase at
+    // every tile boundary: an odd count gets one dummy step that multiplies the tile's last bank
+    // block with an all-zero query block (the query operand holds one such block at index nkb).
+    const int real_steps = DT == 0 ? nkb * 2 : nkb;
+    const int nsteps = real_steps + (real_steps & 1);
+    u32x4_t gbA[8], gbB[8], gq[QCH];
 
-    auto gload = [&](int step) __attribute__((always_inline)) {
+    // Bank loads run two steps ahead of the MFMAs (HBM latency), query loads one step (L2 latency).
+    int ld_ti = 0, ld_step = 0, ldq_step = 0;
+    auto gload_q = [&]() __attribute__((always_inline)) {
+        const uint16_t* qb = qop + ((int64_t)ldq_step * Bp + q0) * KB;
+#pragma unroll
+        for (int i = 0; i < QCH; ++i) gq[i] = *reinterpret_cast<const u32x4_t*>(qb + (i * 256 + tid) * 8);
+        if (++ldq_step == nsteps) ldq_step = 0;
+    };
+    auto gload = [&](u32x4_t (&gb)[8]) __attribute__((always_inline)) {
+        const int64_t t = level_tile(L, first_j + ld_ti * stride_j);
         if constexpr (DT == 0) {
-            const float* blk = static_cast<const float*>(store_) + (t * nkb + (step >> 1)) * (int64_t)BLOCK_ELEMS + (step & 1) * 32;
+            const float* blk = static_cast<const float*>(store_) + (t * nkb + (ld_step >> 1)) * (int64_t)BLOCK_ELEMS + (ld_step & 1) * 32;
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 int g = i * 256 + tid, r = g >> 3, c4 = g & 7;
                 gb[i] = *reinterpret_cast<const u32x4_t*>(blk + r * KB + c4 * 4);
             }
         } else {
-            const uint16_t* blk = static_cast<const uint16_t*>(store_) + (t * nkb + step) * (int64_t)BLOCK_ELEMS;
+            const int kb = ld_step < real_steps ? ld_step : real_steps - 1;
+            const uint16_t* blk = static_cast<const uint16_t*>(store_) + (t * nkb + kb) * (int64_t)BLOCK_ELEMS;
 #pragma unroll
             for (int i = 0; i < 8; ++i) gb[i] = *reinterpret_cast<const u32x4_t*>(blk + (i * 256 + tid) * 8);
         }
-        const uint16_t* qb = qop + ((int64_t)step * Bp + q0) * KB;
-#pragma unroll
-        for (int i = 0; i < QCH; ++i) gq[i] = *reinterpret_cast<const u32x4_t*>(qb + (i * 256 + tid) * 8);
+        // past the last step the cursor stays on the last tile: the two loads issued there are never
+        // consumed, but keeping every phase free of branches lets the loads stay in flight across it
+        if (++ld_step == nsteps) { ld_step = 0; if (ld_ti + 1 < my_tiles) ++ld_ti; }
     };
-    auto lstore = [&](int s) __attribute__((always_inline)) {
+    auto lstore = [&](int s, u32x4_t (&gb)[8]) __attribute__((always_inline)) {
         if constexpr (DT == 0) {
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
@@ -138,135 +157,196 @@ __global__ __launch_bounds__(256) void k_scan_mfma(const void* __restrict__ stor
 #pragma unroll
         for (int i = 0; i < QCH; ++i) *reinterpret_cast<u32x4_t*>(sq(s) + (i * 256 + tid) * 16) = gq[i];
     };
-    auto frag = [&](const unsigned char* base, int row, int chunk) __attribute__((always_inline)) {
-        return *reinterpret_cast<const u32x4_t*>(base + row * 128 + swz16(chunk, row) * 16);
+    // Operand addresses.  Row (block*32 + l32) of an operand tile, logical chunk c = 2*k4 + half:
+    // byte offset = block*4096 + l32*128 + ((c ^ f(l32)) * 16), the swizzle depending on l32 only.
+    // So four per-lane offsets per operand (k4 = 0..3, the wave's first block folded in) serve every
+    // block, both stages and all k-steps; the rest of the address is a compile-time constant.
+    uint32_t offA[4], offB[4];
+#pragma unroll
+    for (int k4 = 0; k4 < 4; ++k4) {
+        const uint32_t o = l32 * 128 + swz16(2 * k4 + half, l32) * 16;
+        offA[k4] = o + STAGE_BANK_BYTES + wq * MQ * 4096;
+        offB[k4] = o + wr * MR * 4096;
+    }
+    auto frag = [&](int s, uint32_t off, int block) __attribute__((always_inline)) {
+        return *reinterpret_cast<const u32x4_t*>(smem + off + (s * STAGE_BYTES + block * 4096));
     };
-    auto compute = [&](int s) __attribute__((always_inline)) {
-        const int half = lane >> 5, l32 = lane & 31;
+    auto compute = [&](int s, auto first_c) __attribute__((always_inline)) {
+        constexpr bool FIRST = decltype(first_c)::value;
         if constexpr (DT == 0) {
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) {
                 u32x4_t ah[MQ], al[MQ], bh[MR], bl[MR];
 #pragma unroll
-                for (int a = 0; a < MQ; ++a) {
-                    int row = (wq * MQ + a) * 32 + l32;
-                    ah[a] = frag(sq(s), row, 2 * ks + half); al[a] = frag(sq(s), row, 4 + 2 * ks + half);
-                }
+                for (int a = 0; a < MQ; ++a) { ah[a] = frag(s, offA[ks], a); al[a] = frag(s, offA[2 + ks], a); }
 #pragma unroll
-                for (int b = 0; b < MR; ++b) {
-                    int row = (wr * MR + b) * 32 + l32;
-                    bh[b] = frag(sbank(s), row, 2 * ks + half); bl[b] = frag(sbank(s), row, 4 + 2 * ks + half);
+                for (int b = 0; b < MR; ++b) { bh[b] = frag(s, offB[ks], b); bl[b] = frag(s, offB[2 + ks], b); }
+#pragma unroll
+                for (int a = 0; a < MQ; ++a)
+#pragma unroll
+                    for (int b = 0; b < MR; ++b) {
+                        if (FIRST && ks == 0) { f32x16_t z = {0.f}; acc[a][b] = mfma32<1>(al[a], bh[b], z); }
+                        else acc[a][b] = mfma32<1>(al[a], bh[b], acc[a][b]);
+                        acc[a][b] = mfma32<1>(ah[a], bl[b], acc[a][b]);
+                        acc[a][b] = mfma32<1>(ah[a], bh[b], acc[a][b]);
+                    }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        } else {
+            // Operand fragments are double buffered by hand (those of k-step ks+1 are read from LDS
+            // while the MFMAs of ks run) and the scheduler is fenced per k-step, which bounds the
+            // live fragment registers to two k-steps' worth.
+            u32x4_t af[2][MQ], bf[2][MR];
+#pragma unroll
+            for (int a = 0; a < MQ; ++a) af[0][a] = frag(s, offA[0], a);
+#pragma unroll
+            for (int b = 0; b < MR; ++b) bf[0][b] = frag(s, offB[0], b);
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                if (ks < 3) {
+#pragma unroll
+                    for (int a = 0; a < MQ; ++a) af[(ks + 1) & 1][a] = frag(s, offA[ks + 1], a);
+#pragma unroll
+                    for (int b = 0; b < MR; ++b) bf[(ks + 1) & 1][b] = frag(s, offB[ks + 1], b);
                 }
 #pragma unroll
                 for (int a = 0; a < MQ; ++a)
 #pragma unroll
                     for (int b = 0; b < MR; ++b) {
-                        acc[a][b] = mfma32<1>(al[a], bh[b], acc[a][b]);
-                        acc[a][b] = mfma32<1>(ah[a], bl[b], acc[a][b]);
-                        acc[a][b] = mfma32<1>(ah[a], bh[b], acc[a][b]);
+                        if (FIRST && ks == 0) { f32x16_t z = {0.f}; acc[a][b] = mfma32<DT>(af[0][a], bf[0][b], z); }
+                        else acc[a][b] = mfma32<DT>(af[ks & 1][a], bf[ks & 1][b], acc[a][b]);
                     }
-            }
-        } else {
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                u32x4_t af[MQ], bf[MR];
-#pragma unroll
-                for (int a = 0; a < MQ; ++a) af[a] = frag(sq(s), (wq * MQ + a) * 32 + l32, 2 * ks + half);
-#pragma unroll
-                for (int b = 0; b < MR; ++b) bf[b] = frag(sbank(s), (wr * MR + b) * 32 + l32, 2 * ks + half);
-#pragma unroll
-                for (int a = 0; a < MQ; ++a)
-#pragma unroll
-                    for (int b = 0; b < MR; ++b) acc[a][b] = mfma32<DT>(af[a], bf[b], acc[a][b]);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
     };
 
-    gload(0);
-    lstore(0);
-    __syncthreads();
-    for (int step = 0; step < nsteps; ++step) {
-        const int s = step & 1;
-        if (step + 1 < nsteps) gload(step + 1);
-        compute(s);
-        if (step + 1 < nsteps) lstore(s ^ 1);
-        __syncthreads();
-    }
-
-    // ---- epilogue ----
-    const int half = lane >> 5, l32 = lane & 31;
-    if (L.rho == 0) {
-        // Sparsest pass: no threshold yet, every row is kept.  Slot = position of the row in this
-        // pass, so no counter is needed (the count was preset to the pass's number of valid rows).
+    // ---- per-tile epilogue (all lanes of the workgroup call it together) ----
+    auto epilogue = [&](int ti) __attribute__((always_inline)) {
+        const int j = first_j + ti * stride_j;
+        const int64_t t = level_tile(L, j);
+        // The lane coordinates are re-derived from an opaque zero, so that the many per-lane output
+        // addresses below are computed here, once per tile, instead of being hoisted out of the
+        // k-loop and kept (spilled) across it.
+        if (L.rho == 0) {
+            // Sparsest pass: no threshold yet, every row is kept.  Slot = position of the row in
+            // this pass, so no counter is needed (the count was preset to the pass's valid rows).
 #pragma unroll
-        for (int b = 0; b < MR; ++b) {
-            const int rt = (wr * MR + b) * 32 + l32;
-            const int64_t id = t * TILE_ROWS + rt;
-            if (id >= N) continue;
-            const float inve = invnorm[id];
-            const int64_t pos = (int64_t)j * TILE_ROWS + rt;
+            for (int b = 0; b < MR; ++b) {
+                int opaque = 0;
+                asm volatile("" : "+v"(opaque));
+                const int half = (lane >> 5) + opaque, l32 = (lane & 31) + opaque;
+                const int rt = (wr * MR + b) * 32 + l32;
+                const int64_t id = t * TILE_ROWS + rt;
+                if (id < N) {
+                    const float inve = invnorm[id];
+                    const int64_t pos = (int64_t)j * TILE_ROWS + rt;
 #pragma unroll
-            for (int a = 0; a < MQ; ++a)
+                    for (int a = 0; a < MQ; ++a) {
+                        int opq = 0;
+                        asm volatile("" : "+v"(opq));
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int ql = (wq * MQ + a) * 32 + 4 * half + 8 * (r >> 2) + (r & 3);
-                    surv[(int64_t)(q0 + ql) * SURV_CAP + pos] = pack_key(acc[a][b][r] * inve * invq_s[ql], (int32_t)id);
-                }
-        }
-        return;
-    }
-    // Filter against the per-query thresholds.  Survivors (rare) go to a workgroup list in LDS first,
-    // so that the global slot counters are bumped once per (workgroup, query) and all at the same
-    // time, instead of one dependent device-wide atomic per survivor.
-    constexpr int LCAP = scan_mfma_list_cap<QT>();
-    uint64_t* lkey = reinterpret_cast<uint64_t*>(smem);
-    uint32_t* lq = reinterpret_cast<uint32_t*>(smem + LCAP * 8);
-#pragma unroll
-    for (int b = 0; b < MR; ++b) {
-        const int64_t id = t * TILE_ROWS + (wr * MR + b) * 32 + l32;
-        const bool valid = id < N;
-        const float inve = valid ? invnorm[id] : 0.f;
-#pragma unroll
-        for (int a = 0; a < MQ; ++a) {
-            const int qb = (wq * MQ + a) * 32 + 4 * half;     // local query of register 0
-            uint32_t m = 0;
-            float v[16];
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                v[r] = acc[a][b][r] * inve;
-                m |= (uint32_t)(v[r] >= thr_s[qb + 8 * (r >> 2) + (r & 3)]) << r;
-            }
-            if (!valid) m = 0;
-            if (m) {
-                uint32_t slot = atomicAdd(total_s, (uint32_t)__popc(m));
-#pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    if (m & (1u << r)) {
-                        const int ql = qb + 8 * (r >> 2) + (r & 3);
-                        const uint64_t key = pack_key(v[r] * invq_s[ql], (int32_t)id);
-                        if (slot < (uint32_t)LCAP) { lkey[slot] = key; lq[slot] = (uint32_t)ql; }
-                        else {   // list full (a very loose threshold): fall back to the direct path
-                            uint32_t pos = atomicAdd(cnt + q0 + ql, 1u);
-                            if (pos < (uint32_t)SURV_CAP) surv[(int64_t)(q0 + ql) * SURV_CAP + pos] = key;
+                        for (int r = 0; r < 16; ++r) {
+                            const int ql = (wq * MQ + a) * 32 + 4 * (half + opq) + 8 * (r >> 2) + (r & 3);
+                            surv[(int64_t)(q0 + ql) * SURV_CAP + pos] = pack_key(acc[a][b][r] * inve * invq_s[ql], (int32_t)id);
                         }
-                        ++slot;
+                        __builtin_amdgcn_sched_barrier(0);
                     }
+                }
+            }
+        } else {
+            // Filter against the per-query thresholds.  Survivors (rare) go to a workgroup list in
+            // LDS first, so that the global slot counters are bumped once per (workgroup, query)
+            // and all at the same time, instead of one dependent device-wide atomic per survivor.
+#pragma unroll
+            for (int b = 0; b < MR; ++b) {
+                int opaque = 0;
+                asm volatile("" : "+v"(opaque));
+                const int half = (lane >> 5) + opaque, l32 = (lane & 31) + opaque;
+                const int64_t id = t * TILE_ROWS + (wr * MR + b) * 32 + l32;
+                const bool valid = id < N;
+                const float inve = valid ? invnorm[id] : 0.f;
+#pragma unroll
+                for (int a = 0; a < MQ; ++a) {
+                    int opq = 0;
+                    asm volatile("" : "+v"(opq));
+                    const int qb = (wq * MQ + a) * 32 + 4 * (half + opq);   // local query of register 0
+                    uint32_t m = 0;
+                    float v[16];
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        v[r] = acc[a][b][r] * inve;
+                        m |= (uint32_t)(v[r] >= thr_s[qb + 8 * (r >> 2) + (r & 3)]) << r;
+                    }
+                    if (!valid) m = 0;
+                    if (m) {
+                        uint32_t slot = atomicAdd(total_s, (uint32_t)__popc(m));
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            if (m & (1u << r)) {
+                                const int ql = qb + 8 * (r >> 2) + (r & 3);
+                                const uint64_t key = pack_key(v[r] * invq_s[ql], (int32_t)id);
+                                if (slot < (uint32_t)SCAN_LIST_CAP) { lkey[slot] = key; lq[slot] = (uint32_t)ql; }
+                                else {   // list full (a very loose threshold): fall back to the direct path
+                                    uint32_t pos = atomicAdd(cnt + q0 + ql, 1u);
+                                    if (pos < (uint32_t)SURV_CAP) surv[(int64_t)(q0 + ql) * SURV_CAP + pos] = key;
+                                }
+                                ++slot;
+                            }
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            __syncthreads();
+            const uint32_t total = *total_s < (uint32_t)SCAN_LIST_CAP ? *total_s : (uint32_t)SCAN_LIST_CAP;
+            if (total) {                                           // uniform across the workgroup
+                for (uint32_t e = tid; e < total; e += 256) {
+                    uint32_t ql = lq[e];
+                    lq[e] = ql | (atomicAdd(cnt_s + ql, 1u) << 16);   // rank among this tile's entries of ql
+                }
+                __syncthreads();
+                for (int i = tid; i < QT; i += 256) {
+                    uint32_t c = cnt_s[i];
+                    base_s[i] = c ? atomicAdd(cnt + q0 + i, c) : 0u;
+                    cnt_s[i] = 0;
+                }
+                __syncthreads();
+                for (uint32_t e = tid; e < total; e += 256) {
+                    uint32_t ql = lq[e] & 0xffffu, rank = lq[e] >> 16;
+                    uint32_t pos = base_s[ql] + rank;
+                    if (pos < (uint32_t)SURV_CAP) surv[(int64_t)(q0 + ql) * SURV_CAP + pos] = lkey[e];
+                }
+                __syncthreads();
+                if (tid == 0) *total_s = 0;
             }
         }
-    }
+    };
+
+    // ---- pipeline over the flattened (tile, k-block) sequence; g counts steps over all tiles ----
+    auto phase = [&](int s, u32x4_t (&ld_b)[8], u32x4_t (&st_b)[8], auto first_c) __attribute__((always_inline)) {
+        // LDS stage s holds the current step; registers st_b hold the bank block of the next one;
+        // ld_b is free for the one after that
+        // (query loads first: loads complete in issue order, and the stores at the end of this phase
+        //  wait for the queries of step g+1 but must leave the bank loads of step g+2 in flight)
+        gload_q();
+        gload(ld_b);
+        compute(s, first_c);
+        lstore(s ^ 1, st_b);
+        __syncthreads();
+    };
+    gload(gbA);
+    gload_q();
+    gload(gbB);
+    lstore(0, gbA);
     __syncthreads();
-    const uint32_t total = *total_s < (uint32_t)LCAP ? *total_s : (uint32_t)LCAP;
-    for (uint32_t e = tid; e < total; e += 256) {
-        uint32_t ql = lq[e];
-        lq[e] = ql | (atomicAdd(cnt_s + ql, 1u) << 16);        // rank within this workgroup's entries of ql
-    }
-    __syncthreads();
-    for (int i = tid; i < QT; i += 256) { uint32_t c = cnt_s[i]; base_s[i] = c ? atomicAdd(cnt + q0 + i, c) : 0u; }
-    __syncthreads();
-    for (uint32_t e = tid; e < total; e += 256) {
-        uint32_t ql = lq[e] & 0xffffu, rank = lq[e] >> 16;
-        uint32_t pos = base_s[ql] + rank;
-        if (pos < (uint32_t)SURV_CAP) surv[(int64_t)(q0 + ql) * SURV_CAP + pos] = lkey[e];
+    for (int ti = 0; ti < my_tiles; ++ti) {
+        phase(0, gbA, gbB, std::true_type{});
+        phase(1, gbB, gbA, std::false_type{});
+        for (int st = 2; st < nsteps; st += 2) {
+            phase(0, gbA, gbB, std::false_type{});
+            phase(1, gbB, gbA, std::false_type{});
+        }
+        epilogue(ti);
     }
 }
 
