@@ -254,7 +254,7 @@ int launch_mfma(evomem* h, hipStream_t st, int Bp, const Level& L) {
     if (!resident[h->device & 15]) {
         HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds));
         int per_cu = 0, cus = 0;
-        HIPCHK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(kern), 256, lds));
+        HIPCHK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(kern), 64 * WQ * WR, lds));
         HIPCHK(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, h->device));
         if (per_cu < 1 || cus < 8) return MEM_EHIP;
         resident[h->device & 15] = per_cu * cus;
@@ -264,7 +264,7 @@ int launch_mfma(evomem* h, hipStream_t st, int Bp, const Level& L) {
     int groups = resident[h->device & 15] / 8 / nqt;
     if (groups < 1) groups = 1;
     if (groups > (L.ntiles + 7) / 8) groups = (L.ntiles + 7) / 8;
-    dim3 grid((unsigned)(8 * nqt * groups)), block(256);
+    dim3 grid((unsigned)(8 * nqt * groups)), block(64 * WQ * WR);
     unsigned char* ws = h->ws;
     hipLaunchKernelGGL(kern, grid, block, lds, st, (const void*)h->store, (const float*)h->invnorm,
                        (const uint16_t*)(ws + h->w.qop), (const float*)(ws + h->w.invq), (const float*)(ws + h->w.thr),
@@ -279,7 +279,7 @@ int launch_mfma_dt(evomem* h, hipStream_t st, int Bp, int qt, const Level& L) {
         case 32: return launch_mfma<DT, 1, 1, 2, 4>(h, st, Bp, L);
         case 64: return launch_mfma<DT, 2, 1, 2, 4>(h, st, Bp, L);
         case 128: return launch_mfma<DT, 2, 2, 4, 2>(h, st, Bp, L);
-        default: return launch_mfma<DT, 4, 2, 4, 2>(h, st, Bp, L);
+        default: return launch_mfma<DT, 4, 2, 2, 4>(h, st, Bp, L);   // 8 wavefronts, 128 x 64 each
     }
 }
 

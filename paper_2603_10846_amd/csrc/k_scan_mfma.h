@@ -57,14 +57,16 @@ template <int QT> constexpr int scan_mfma_lds_bytes() {
 // DT: 0 fp32 store (bf16 split), 1 bf16, 2 f16.  Wave grid WQ x WR, each wave MQ x MR blocks of 32x32.
 // gridDim.x is a multiple of 8 * (Bp / QT).
 template <int DT, int MQ, int WQ, int MR, int WR>
-__global__ __launch_bounds__(256) void k_scan_mfma(const void* __restrict__ store_, const float* __restrict__ invnorm,
+__global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restrict__ store_, const float* __restrict__ invnorm,
                                                    const uint16_t* __restrict__ qop, const float* __restrict__ invq,
                                                    const float* __restrict__ thr, uint32_t* __restrict__ cnt,
                                                    uint64_t* __restrict__ surv, int64_t N, int nkb, int Bp,
                                                    Level L) {
-    static_assert(WQ * WR == 4 && MR * WR == 8, "4 waves, 256 bank rows per workgroup");
+    static_assert((WQ * WR == 4 || WQ * WR == 8) && MR * WR == 8, "4 or 8 waves, 256 bank rows per workgroup");
+    constexpr int NT = 64 * WQ * WR;                   // lanes per workgroup
     constexpr int QT = 32 * MQ * WQ;
-    constexpr int QCH = QT / 32;                       // 16-byte query chunks per lane per stage
+    constexpr int BCH = 2048 / NT;                     // 16-byte bank chunks per lane per stage
+    constexpr int QCH = QT * 8 / NT;                   // 16-byte query chunks per lane per stage
     constexpr int STAGE_BYTES = STAGE_BANK_BYTES + QT * 128;
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -93,7 +95,7 @@ __global__ __launch_bounds__(256) void k_scan_mfma(const void* __restrict__ stor
     uint64_t* lkey = reinterpret_cast<uint64_t*>(base_s + QT);
     uint32_t* lq = reinterpret_cast<uint32_t*>(lkey + SCAN_LIST_CAP);
     uint32_t* total_s = lq + SCAN_LIST_CAP;
-    for (int i = tid; i < QT; i += 256) { thr_s[i] = thr[q0 + i]; invq_s[i] = invq[q0 + i]; cnt_s[i] = 0; }
+    for (int i = tid; i < QT; i += NT) { thr_s[i] = thr[q0 + i]; invq_s[i] = invq[q0 + i]; cnt_s[i] = 0; }
     if (tid == 0) *total_s = 0;
 
     // Accumulators: never zeroed explicitly -- the first MFMA of a tile takes a zero C operand.
@@ -105,40 +107,40 @@ __global__ __launch_bounds__(256) void k_scan_mfma(const void* __restrict__ stor
     // block with an all-zero query block (the query operand holds one such block at index nkb).
     const int real_steps = DT == 0 ? nkb * 2 : nkb;
     const int nsteps = real_steps + (real_steps & 1);
-    u32x4_t gbA[8], gbB[8], gq[QCH];
+    u32x4_t gbA[BCH], gbB[BCH], gq[QCH];
 
     // Bank loads run two steps ahead of the MFMAs (HBM latency), query loads one step (L2 latency).
     int ld_ti = 0, ld_step = 0, ldq_step = 0;
     auto gload_q = [&]() __attribute__((always_inline)) {
         const uint16_t* qb = qop + ((int64_t)ldq_step * Bp + q0) * KB;
 #pragma unroll
-        for (int i = 0; i < QCH; ++i) gq[i] = *reinterpret_cast<const u32x4_t*>(qb + (i * 256 + tid) * 8);
+        for (int i = 0; i < QCH; ++i) gq[i] = *reinterpret_cast<const u32x4_t*>(qb + (i * NT + tid) * 8);
         if (++ldq_step == nsteps) ldq_step = 0;
     };
-    auto gload = [&](u32x4_t (&gb)[8]) __attribute__((always_inline)) {
+    auto gload = [&](u32x4_t (&gb)[BCH]) __attribute__((always_inline)) {
         const int64_t t = level_tile(L, first_j + ld_ti * stride_j);
         if constexpr (DT == 0) {
             const float* blk = static_cast<const float*>(store_) + (t * nkb + (ld_step >> 1)) * (int64_t)BLOCK_ELEMS + (ld_step & 1) * 32;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                int g = i * 256 + tid, r = g >> 3, c4 = g & 7;
+            for (int i = 0; i < BCH; ++i) {
+                int g = i * NT + tid, r = g >> 3, c4 = g & 7;
                 gb[i] = *reinterpret_cast<const u32x4_t*>(blk + r * KB + c4 * 4);
             }
         } else {
             const int kb = ld_step < real_steps ? ld_step : real_steps - 1;
             const uint16_t* blk = static_cast<const uint16_t*>(store_) + (t * nkb + kb) * (int64_t)BLOCK_ELEMS;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) gb[i] = *reinterpret_cast<const u32x4_t*>(blk + (i * 256 + tid) * 8);
+            for (int i = 0; i < BCH; ++i) gb[i] = *reinterpret_cast<const u32x4_t*>(blk + (i * NT + tid) * 8);
         }
         // past the last step the cursor stays on the last tile: the two loads issued there are never
         // consumed, but keeping every phase free of branches lets the loads stay in flight across it
         if (++ld_step == nsteps) { ld_step = 0; if (ld_ti + 1 < my_tiles) ++ld_ti; }
     };
-    auto lstore = [&](int s, u32x4_t (&gb)[8]) __attribute__((always_inline)) {
+    auto lstore = [&](int s, u32x4_t (&gb)[BCH]) __attribute__((always_inline)) {
         if constexpr (DT == 0) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                int g = i * 256 + tid, r = g >> 3, c4 = g & 7;
+            for (int i = 0; i < BCH; ++i) {
+                int g = i * NT + tid, r = g >> 3, c4 = g & 7;
                 float f0 = __uint_as_float(gb[i].x), f1 = __uint_as_float(gb[i].y);
                 float f2 = __uint_as_float(gb[i].z), f3 = __uint_as_float(gb[i].w);
                 float r0, r1, r2, r3;
@@ -152,10 +154,10 @@ __global__ __launch_bounds__(256) void k_scan_mfma(const void* __restrict__ stor
             }
         } else {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4_t*>(sbank(s) + (i * 256 + tid) * 16) = gb[i];
+            for (int i = 0; i < BCH; ++i) *reinterpret_cast<u32x4_t*>(sbank(s) + (i * NT + tid) * 16) = gb[i];
         }
 #pragma unroll
-        for (int i = 0; i < QCH; ++i) *reinterpret_cast<u32x4_t*>(sq(s) + (i * 256 + tid) * 16) = gq[i];
+        for (int i = 0; i < QCH; ++i) *reinterpret_cast<u32x4_t*>(sq(s) + (i * NT + tid) * 16) = gq[i];
     };
     // Operand addresses.  Row (block*32 + l32) of an operand tile, logical chunk c = 2*k4 + half:
     // byte offset = block*4096 + l32*128 + ((c ^ f(l32)) * 16), the swizzle depending on l32 only.
@@ -300,18 +302,18 @@ __global__ __launch_bounds__(256) void k_scan_mfma(const void* __restrict__ stor
             __syncthreads();
             const uint32_t total = *total_s < (uint32_t)SCAN_LIST_CAP ? *total_s : (uint32_t)SCAN_LIST_CAP;
             if (total) {                                           // uniform across the workgroup
-                for (uint32_t e = tid; e < total; e += 256) {
+                for (uint32_t e = tid; e < total; e += NT) {
                     uint32_t ql = lq[e];
                     lq[e] = ql | (atomicAdd(cnt_s + ql, 1u) << 16);   // rank among this tile's entries of ql
                 }
                 __syncthreads();
-                for (int i = tid; i < QT; i += 256) {
+                for (int i = tid; i < QT; i += NT) {
                     uint32_t c = cnt_s[i];
                     base_s[i] = c ? atomicAdd(cnt + q0 + i, c) : 0u;
                     cnt_s[i] = 0;
                 }
                 __syncthreads();
-                for (uint32_t e = tid; e < total; e += 256) {
+                for (uint32_t e = tid; e < total; e += NT) {
                     uint32_t ql = lq[e] & 0xffffu, rank = lq[e] >> 16;
                     uint32_t pos = base_s[ql] + rank;
                     if (pos < (uint32_t)SURV_CAP) surv[(int64_t)(q0 + ql) * SURV_CAP + pos] = lkey[e];
@@ -323,7 +325,7 @@ __global__ __launch_bounds__(256) void k_scan_mfma(const void* __restrict__ stor
     };
 
     // ---- pipeline over the flattened (tile, k-block) sequence; g counts steps over all tiles ----
-    auto phase = [&](int s, u32x4_t (&ld_b)[8], u32x4_t (&st_b)[8], auto first_c) __attribute__((always_inline)) {
+    auto phase = [&](int s, u32x4_t (&ld_b)[BCH], u32x4_t (&st_b)[BCH], auto first_c) __attribute__((always_inline)) {
         // LDS stage s holds the current step; registers st_b hold the bank block of the next one;
         // ld_b is free for the one after that
         // (query loads first: loads complete in issue order, and the stores at the end of this phase
