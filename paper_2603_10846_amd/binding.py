@@ -13,7 +13,8 @@ import subprocess
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libevomem.so")
+# EVOMEM_LIB selects another build of the same library (e.g. one compiled with other flags)
+LIB_PATH = os.environ.get("EVOMEM_LIB") or os.path.join(_HERE, "libevomem.so")
 SRC = os.path.join(_HERE, "csrc", "evomem.hip")
 
 MEM_OK, MEM_EINVAL, MEM_ECAPACITY, MEM_EWORKSPACE, MEM_EHIP, MEM_ESTATE = range(6)

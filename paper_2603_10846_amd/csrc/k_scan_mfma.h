@@ -88,14 +88,14 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
 
     auto sbank = [&](int s) __attribute__((always_inline)) { return smem + s * STAGE_BYTES; };
     auto sq = [&](int s) __attribute__((always_inline)) { return smem + s * STAGE_BYTES + STAGE_BANK_BYTES; };
-    float* thr_s = reinterpret_cast<float*>(smem + 2 * STAGE_BYTES);
-    float* invq_s = thr_s + QT;
+    float* nthr_s = reinterpret_cast<float*>(smem + 2 * STAGE_BYTES);   // negated thresholds
+    float* invq_s = nthr_s + QT;
     uint32_t* cnt_s = reinterpret_cast<uint32_t*>(invq_s + QT);
     uint32_t* base_s = cnt_s + QT;
     uint64_t* lkey = reinterpret_cast<uint64_t*>(base_s + QT);
     uint32_t* lq = reinterpret_cast<uint32_t*>(lkey + SCAN_LIST_CAP);
     uint32_t* total_s = lq + SCAN_LIST_CAP;
-    for (int i = tid; i < QT; i += NT) { thr_s[i] = thr[q0 + i]; invq_s[i] = invq[q0 + i]; cnt_s[i] = 0; }
+    for (int i = tid; i < QT; i += NT) { nthr_s[i] = -thr[q0 + i]; invq_s[i] = invq[q0 + i]; cnt_s[i] = 0; }
     if (tid == 0) *total_s = 0;
 
     // Accumulators: never zeroed explicitly -- the first MFMA of a tile takes a zero C operand.
@@ -107,12 +107,21 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
     // block with an all-zero query block (the query operand holds one such block at index nkb).
     const int real_steps = DT == 0 ? nkb * 2 : nkb;
     const int nsteps = real_steps + (real_steps & 1);
-    u32x4_t gbA[BCH], gbB[BCH], gq[QCH];
+    u32x4_t gbA[BCH], gbB[BCH], gqA[QCH], gqB[QCH];
 
-    // Bank loads run two steps ahead of the MFMAs (HBM latency), query loads one step (L2 latency).
+    // Bank and query loads run two steps ahead of the MFMAs.
+    // Each workgroup starts its k-loop at a different k-block (the order of the k-blocks does not
+    // matter for a dot product): workgroups run in near lock-step over tiles that are 2^n bytes
+    // apart, and without the rotation they would all pull from the same few HBM channels at once.
+    const int rot = (int)((blockIdx.x * 7u) % (unsigned)real_steps);
+    auto rotated = [&](int step) __attribute__((always_inline)) {   // logical step -> k-step actually loaded
+        if (step >= real_steps) return step;                          // the dummy step stays last
+        int k = step + rot;
+        return k >= real_steps ? k - real_steps : k;
+    };
     int ld_ti = 0, ld_step = 0, ldq_step = 0;
-    auto gload_q = [&]() __attribute__((always_inline)) {
-        const uint16_t* qb = qop + ((int64_t)ldq_step * Bp + q0) * KB;
+    auto gload_q = [&](u32x4_t (&gq)[QCH]) __attribute__((always_inline)) {
+        const uint16_t* qb = qop + ((int64_t)rotated(ldq_step) * Bp + q0) * KB;
 #pragma unroll
         for (int i = 0; i < QCH; ++i) gq[i] = *reinterpret_cast<const u32x4_t*>(qb + (i * NT + tid) * 8);
         if (++ldq_step == nsteps) ldq_step = 0;
@@ -120,14 +129,14 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
     auto gload = [&](u32x4_t (&gb)[BCH]) __attribute__((always_inline)) {
         const int64_t t = level_tile(L, first_j + ld_ti * stride_j);
         if constexpr (DT == 0) {
-            const float* blk = static_cast<const float*>(store_) + (t * nkb + (ld_step >> 1)) * (int64_t)BLOCK_ELEMS + (ld_step & 1) * 32;
+            const float* blk = static_cast<const float*>(store_) + (t * nkb + (rotated(ld_step) >> 1)) * (int64_t)BLOCK_ELEMS + (rotated(ld_step) & 1) * 32;
 #pragma unroll
             for (int i = 0; i < BCH; ++i) {
                 int g = i * NT + tid, r = g >> 3, c4 = g & 7;
                 gb[i] = *reinterpret_cast<const u32x4_t*>(blk + r * KB + c4 * 4);
             }
         } else {
-            const int kb = ld_step < real_steps ? ld_step : real_steps - 1;
+            const int kb = ld_step < real_steps ? rotated(ld_step) : real_steps - 1;
             const uint16_t* blk = static_cast<const uint16_t*>(store_) + (t * nkb + kb) * (int64_t)BLOCK_ELEMS;
 #pragma unroll
             for (int i = 0; i < BCH; ++i) gb[i] = *reinterpret_cast<const u32x4_t*>(blk + (i * NT + tid) * 8);
@@ -136,7 +145,7 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
         // consumed, but keeping every phase free of branches lets the loads stay in flight across it
         if (++ld_step == nsteps) { ld_step = 0; if (ld_ti + 1 < my_tiles) ++ld_ti; }
     };
-    auto lstore = [&](int s, u32x4_t (&gb)[BCH]) __attribute__((always_inline)) {
+    auto lstore = [&](int s, u32x4_t (&gb)[BCH], u32x4_t (&gq)[QCH]) __attribute__((always_inline)) {
         if constexpr (DT == 0) {
 #pragma unroll
             for (int i = 0; i < BCH; ++i) {
@@ -173,7 +182,9 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
     auto frag = [&](int s, uint32_t off, int block) __attribute__((always_inline)) {
         return *reinterpret_cast<const u32x4_t*>(smem + off + (s * STAGE_BYTES + block * 4096));
     };
-    auto compute = [&](int s, auto first_c) __attribute__((always_inline)) {
+    // `mid` (the LDS stores of the next step's operands) runs between the second and third k-step, so
+    // that those stores overlap the MFMAs instead of forming a separate period before the barrier.
+    auto compute = [&](int s, auto first_c, auto mid) __attribute__((always_inline)) {
         constexpr bool FIRST = decltype(first_c)::value;
         if constexpr (DT == 0) {
 #pragma unroll
@@ -193,33 +204,82 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
                         acc[a][b] = mfma32<1>(ah[a], bh[b], acc[a][b]);
                     }
                 __builtin_amdgcn_sched_barrier(0);
+                if (ks == 0) { mid(); __builtin_amdgcn_sched_barrier(0); }
             }
         } else {
             // Operand fragments are double buffered by hand (those of k-step ks+1 are read from LDS
             // while the MFMAs of ks run) and the scheduler is fenced per k-step, which bounds the
             // live fragment registers to two k-steps' worth.
-            u32x4_t af[2][MQ], bf[2][MR];
+            // (With two wavefronts per SIMD the other wavefront's MFMAs cover the LDS latency, and the
+            // registers are better spent on loads in flight: fragments are then single buffered.)
+            constexpr int FB = NT == 512 ? 0 : 1;      // index mask of the fragment buffers
+            u32x4_t af[FB + 1][MQ], bf[FB + 1][MR];
 #pragma unroll
             for (int a = 0; a < MQ; ++a) af[0][a] = frag(s, offA[0], a);
 #pragma unroll
             for (int b = 0; b < MR; ++b) bf[0][b] = frag(s, offB[0], b);
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {
-                if (ks < 3) {
+                if (ks < 3 && FB) {
 #pragma unroll
-                    for (int a = 0; a < MQ; ++a) af[(ks + 1) & 1][a] = frag(s, offA[ks + 1], a);
+                    for (int a = 0; a < MQ; ++a) af[(ks + 1) & FB][a] = frag(s, offA[ks + 1], a);
 #pragma unroll
-                    for (int b = 0; b < MR; ++b) bf[(ks + 1) & 1][b] = frag(s, offB[ks + 1], b);
+                    for (int b = 0; b < MR; ++b) bf[(ks + 1) & FB][b] = frag(s, offB[ks + 1], b);
                 }
 #pragma unroll
                 for (int a = 0; a < MQ; ++a)
 #pragma unroll
                     for (int b = 0; b < MR; ++b) {
                         if (FIRST && ks == 0) { f32x16_t z = {0.f}; acc[a][b] = mfma32<DT>(af[0][a], bf[0][b], z); }
-                        else acc[a][b] = mfma32<DT>(af[ks & 1][a], bf[ks & 1][b], acc[a][b]);
+                        else acc[a][b] = mfma32<DT>(af[ks & FB][a], bf[ks & FB][b], acc[a][b]);
                     }
                 __builtin_amdgcn_sched_barrier(0);
+                if (ks == 1) { mid(); __builtin_amdgcn_sched_barrier(0); }
+                if (ks < 3 && !FB) {
+#pragma unroll
+                    for (int a = 0; a < MQ; ++a) af[0][a] = frag(s, offA[ks + 1], a);
+#pragma unroll
+                    for (int b = 0; b < MR; ++b) bf[0][b] = frag(s, offB[ks + 1], b);
+                }
             }
+        }
+    };
+
+    // Write the workgroup's staged survivors to the per-query lists (all lanes call it together):
+    // rank the entries of each query with LDS atomics, reserve that many slots with one device-wide
+    // integer atomic per query that has any, copy.
+    auto flush = [&]() __attribute__((always_inline)) {
+        const uint32_t total = *total_s < (uint32_t)SCAN_LIST_CAP ? *total_s : (uint32_t)SCAN_LIST_CAP;
+        for (uint32_t e = tid; e < total; e += NT) {
+            uint32_t ql = lq[e];
+            lq[e] = ql | (atomicAdd(cnt_s + ql, 1u) << 16);   // rank among the staged entries of ql
+        }
+        __syncthreads();
+        for (int i = tid; i < QT; i += NT) {
+            uint32_t c = cnt_s[i];
+            base_s[i] = c ? atomicAdd(cnt + q0 + i, c) : 0u;
+            cnt_s[i] = 0;
+        }
+        __syncthreads();
+        for (uint32_t e = tid; e < total; e += NT) {
+            uint32_t ql = lq[e] & 0xffffu, rank = lq[e] >> 16;
+            uint32_t pos = base_s[ql] + rank;
+            if (pos < (uint32_t)SURV_CAP) surv[(int64_t)(q0 + ql) * SURV_CAP + pos] = lkey[e];
+        }
+        __syncthreads();
+        if (tid == 0) *total_s = 0;
+        __syncthreads();
+    };
+
+    // Inverse norms of this lane's MR bank rows of the current tile; loaded when the tile starts so
+    // that they have arrived long before the epilogue needs them.
+    float inv_r[MR];
+    auto load_invnorm = [&](int ti) __attribute__((always_inline)) {
+        const int64_t t = level_tile(L, first_j + ti * stride_j);
+#pragma unroll
+        for (int b = 0; b < MR; ++b) {
+            int64_t id = t * TILE_ROWS + (wr * MR + b) * 32 + l32;
+            inv_r[b] = invnorm[id < N ? id : N - 1];
         }
     };
 
@@ -241,7 +301,7 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
                 const int rt = (wr * MR + b) * 32 + l32;
                 const int64_t id = t * TILE_ROWS + rt;
                 if (id < N) {
-                    const float inve = invnorm[id];
+                    const float inve = inv_r[b];
                     const int64_t pos = (int64_t)j * TILE_ROWS + rt;
 #pragma unroll
                     for (int a = 0; a < MQ; ++a) {
@@ -260,93 +320,106 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
             // Filter against the per-query thresholds.  Survivors (rare) go to a workgroup list in
             // LDS first, so that the global slot counters are bumped once per (workgroup, query)
             // and all at the same time, instead of one dependent device-wide atomic per survivor.
+            // Pass 1, every score: d = score * invnorm - threshold (one FMA against the negated
+            // threshold kept in LDS), and the largest d of each 32x32 block (max3).  Only where that
+            // is >= 0 does a lane build the block's 16-bit survivor mask, from the sign bits of d.
+            uint32_t msk[MQ * MR];
+            uint32_t mine = 0;
 #pragma unroll
             for (int b = 0; b < MR; ++b) {
                 int opaque = 0;
                 asm volatile("" : "+v"(opaque));
                 const int half = (lane >> 5) + opaque, l32 = (lane & 31) + opaque;
-                const int64_t id = t * TILE_ROWS + (wr * MR + b) * 32 + l32;
-                const bool valid = id < N;
-                const float inve = valid ? invnorm[id] : 0.f;
+                const bool valid = t * TILE_ROWS + (wr * MR + b) * 32 + l32 < N;
+                const float inve = inv_r[b];
 #pragma unroll
                 for (int a = 0; a < MQ; ++a) {
-                    int opq = 0;
-                    asm volatile("" : "+v"(opq));
-                    const int qb = (wq * MQ + a) * 32 + 4 * (half + opq);   // local query of register 0
+                    const int qb = (wq * MQ + a) * 32 + 4 * half;     // local query of register 0
+                    float d[16];
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) d[r] = fmaf(acc[a][b][r], inve, nthr_s[qb + 8 * (r >> 2) + (r & 3)]);
+                    float mx = fmaxf(d[0], d[1]);
+#pragma unroll
+                    for (int r = 2; r < 16; r += 2) mx = fmaxf(mx, fmaxf(d[r], d[r + 1]));
                     uint32_t m = 0;
-                    float v[16];
+                    if (valid && mx >= 0.f) {
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        v[r] = acc[a][b][r] * inve;
-                        m |= (uint32_t)(v[r] >= thr_s[qb + 8 * (r >> 2) + (r & 3)]) << r;
+                        for (int r = 0; r < 16; ++r) m |= ((~__float_as_uint(d[r])) >> 31) << r;
                     }
-                    if (!valid) m = 0;
-                    if (m) {
-                        uint32_t slot = atomicAdd(total_s, (uint32_t)__popc(m));
-#pragma unroll
-                        for (int r = 0; r < 16; ++r)
-                            if (m & (1u << r)) {
-                                const int ql = qb + 8 * (r >> 2) + (r & 3);
-                                const uint64_t key = pack_key(v[r] * invq_s[ql], (int32_t)id);
-                                if (slot < (uint32_t)SCAN_LIST_CAP) { lkey[slot] = key; lq[slot] = (uint32_t)ql; }
-                                else {   // list full (a very loose threshold): fall back to the direct path
-                                    uint32_t pos = atomicAdd(cnt + q0 + ql, 1u);
-                                    if (pos < (uint32_t)SURV_CAP) surv[(int64_t)(q0 + ql) * SURV_CAP + pos] = key;
-                                }
-                                ++slot;
-                            }
-                    }
+                    msk[a * MR + b] = m;
+                    mine += __popc(m);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
-            __syncthreads();
-            const uint32_t total = *total_s < (uint32_t)SCAN_LIST_CAP ? *total_s : (uint32_t)SCAN_LIST_CAP;
-            if (total) {                                           // uniform across the workgroup
-                for (uint32_t e = tid; e < total; e += NT) {
-                    uint32_t ql = lq[e];
-                    lq[e] = ql | (atomicAdd(cnt_s + ql, 1u) << 16);   // rank among this tile's entries of ql
+            // Slots: one LDS atomic per wavefront and tile (prefix sum of the lanes' counts).
+            uint32_t incl = mine;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) { uint32_t up = __shfl_up(incl, o, 64); if (lane >= o) incl += up; }
+            const uint32_t wave_total = __shfl(incl, 63, 64);
+            if (wave_total) {                                   // uniform within the wavefront
+                uint32_t base = 0;
+                if (lane == 63) base = atomicAdd(total_s, wave_total);
+                uint32_t slot = __shfl(base, 63, 64) + incl - mine;
+                // Pass 2, survivors only.
+#pragma unroll
+                for (int b = 0; b < MR; ++b) {
+                    int opaque = 0;
+                    asm volatile("" : "+v"(opaque));
+                    const int half = (lane >> 5) + opaque, l32 = (lane & 31) + opaque;
+                    const int32_t id = (int32_t)(t * TILE_ROWS + (wr * MR + b) * 32 + l32);
+                    const float inve = inv_r[b];
+#pragma unroll
+                    for (int a = 0; a < MQ; ++a) {
+                        const uint32_t m = msk[a * MR + b];
+                        if (m) {
+                            const int qb = (wq * MQ + a) * 32 + 4 * half;
+#pragma unroll
+                            for (int r = 0; r < 16; ++r)
+                                if (m & (1u << r)) {
+                                    const int ql = qb + 8 * (r >> 2) + (r & 3);
+                                    const uint64_t key = pack_key(acc[a][b][r] * inve * invq_s[ql], id);
+                                    if (slot < (uint32_t)SCAN_LIST_CAP) { lkey[slot] = key; lq[slot] = (uint32_t)ql; }
+                                    else {   // list full (a very loose threshold): fall back to the direct path
+                                        uint32_t pos = atomicAdd(cnt + q0 + ql, 1u);
+                                        if (pos < (uint32_t)SURV_CAP) surv[(int64_t)(q0 + ql) * SURV_CAP + pos] = key;
+                                    }
+                                    ++slot;
+                                }
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
                 }
-                __syncthreads();
-                for (int i = tid; i < QT; i += NT) {
-                    uint32_t c = cnt_s[i];
-                    base_s[i] = c ? atomicAdd(cnt + q0 + i, c) : 0u;
-                    cnt_s[i] = 0;
-                }
-                __syncthreads();
-                for (uint32_t e = tid; e < total; e += NT) {
-                    uint32_t ql = lq[e] & 0xffffu, rank = lq[e] >> 16;
-                    uint32_t pos = base_s[ql] + rank;
-                    if (pos < (uint32_t)SURV_CAP) surv[(int64_t)(q0 + ql) * SURV_CAP + pos] = lkey[e];
-                }
-                __syncthreads();
-                if (tid == 0) *total_s = 0;
             }
+            // The list is carried from tile to tile and written out only when it is half full (and
+            // once at the end), so the device-wide round trip below is paid every few tiles.
+            __syncthreads();
+            if (*total_s >= (uint32_t)(SCAN_LIST_CAP / 2) || ti == my_tiles - 1) flush();   // uniform
         }
     };
 
     // ---- pipeline over the flattened (tile, k-block) sequence; g counts steps over all tiles ----
-    auto phase = [&](int s, u32x4_t (&ld_b)[BCH], u32x4_t (&st_b)[BCH], auto first_c) __attribute__((always_inline)) {
+    auto phase = [&](int s, u32x4_t (&ld_b)[BCH], u32x4_t (&ld_q)[QCH], u32x4_t (&st_b)[BCH], u32x4_t (&st_q)[QCH],
+                     auto first_c) __attribute__((always_inline)) {
         // LDS stage s holds the current step; registers st_b hold the bank block of the next one;
         // ld_b is free for the one after that
-        // (query loads first: loads complete in issue order, and the stores at the end of this phase
-        //  wait for the queries of step g+1 but must leave the bank loads of step g+2 in flight)
-        gload_q();
+        gload_q(ld_q);
         gload(ld_b);
-        compute(s, first_c);
-        lstore(s ^ 1, st_b);
+        compute(s, first_c, [&]() __attribute__((always_inline)) { lstore(s ^ 1, st_b, st_q); });
         __syncthreads();
     };
     gload(gbA);
-    gload_q();
+    gload_q(gqA);
     gload(gbB);
-    lstore(0, gbA);
+    gload_q(gqB);
+    lstore(0, gbA, gqA);
     __syncthreads();
     for (int ti = 0; ti < my_tiles; ++ti) {
-        phase(0, gbA, gbB, std::true_type{});
-        phase(1, gbB, gbA, std::false_type{});
+        load_invnorm(ti);
+        phase(0, gbA, gqA, gbB, gqB, std::true_type{});
+        phase(1, gbB, gqB, gbA, gqA, std::false_type{});
         for (int st = 2; st < nsteps; st += 2) {
-            phase(0, gbA, gbB, std::false_type{});
-            phase(1, gbB, gbA, std::false_type{});
+            phase(0, gbA, gqA, gbB, gqB, std::false_type{});
+            phase(1, gbB, gqB, gbA, gqA, std::false_type{});
         }
         epilogue(ti);
     }
