@@ -359,6 +359,7 @@ extern "C" int mem_retrieve(evomem_t* h, const float* queries_dev, int B, int st
     // rounding margin of the scan's fp32 similarities
     float eps = (float)(h->nkb * KB) * 5.97e-8f + 1e-6f;
     if (h->dtype == MEM_F32 && !gemv) eps += 2e-5f;      // bf16 hi/lo split of fp32 values
+    if (!gemv) eps += 2e-5f;                             // threshold * norm carried as 16-bit hi/lo pairs
     const float margin = 2.f * eps;
 
     if (h->N > 0) {

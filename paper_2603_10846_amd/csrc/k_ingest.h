@@ -179,7 +179,10 @@ __global__ __launch_bounds__(256) void k_prep_queries(const float* __restrict__ 
         double inv = live ? 1.0 / sqrt(red[0]) : 0.0;
         invq64[b] = inv;
         invq[b] = (float)inv;
-        thr[b] = live ? -INFINITY : INFINITY;
+        // "No threshold yet" is a finite floor below every reachable value (the scan compares
+        // dot * invnorm, which lies in [-|q|, |q|]); empty slots get a threshold their all-zero query
+        // can never reach.  Finite values keep the scan's arithmetic free of inf - inf.
+        thr[b] = live ? (float)(-2.0 / inv) : 1.0f;
         cnt[b] = live ? cnt0 : 0u;     // rows the sparsest pass will write without counting
     }
 }

@@ -68,6 +68,9 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
     constexpr int BCH = 2048 / NT;                     // 16-byte bank chunks per lane per stage
     constexpr int QCH = QT * 8 / NT;                   // 16-byte query chunks per lane per stage
     constexpr int STAGE_BYTES = STAGE_BANK_BYTES + QT * 128;
+    // 16-bit float type of the MFMA operands (bf16 also for fp32 stores, which are split into bf16)
+    auto enc16 = [](float x) __attribute__((always_inline)) { return DT == 2 ? f2f16_rne(x) : f2bf16_rne(x); };
+    auto dec16 = [](uint16_t h) __attribute__((always_inline)) { return DT == 2 ? f16_to_f(h) : bf16_to_f(h); };
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wq = wave / WR, wr = wave % WR;
@@ -88,17 +91,23 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
 
     auto sbank = [&](int s) __attribute__((always_inline)) { return smem + s * STAGE_BYTES; };
     auto sq = [&](int s) __attribute__((always_inline)) { return smem + s * STAGE_BYTES + STAGE_BANK_BYTES; };
-    float* nthr_s = reinterpret_cast<float*>(smem + 2 * STAGE_BYTES);   // negated thresholds
-    float* invq_s = nthr_s + QT;
+    uint32_t* thp_s = reinterpret_cast<uint32_t*>(smem + 2 * STAGE_BYTES);   // thresholds as (hi | lo << 16), 16-bit floats
+    float* invq_s = reinterpret_cast<float*>(thp_s + QT);
     uint32_t* cnt_s = reinterpret_cast<uint32_t*>(invq_s + QT);
     uint32_t* base_s = cnt_s + QT;
     uint64_t* lkey = reinterpret_cast<uint64_t*>(base_s + QT);
     uint32_t* lq = reinterpret_cast<uint32_t*>(lkey + SCAN_LIST_CAP);
     uint32_t* total_s = lq + SCAN_LIST_CAP;
-    for (int i = tid; i < QT; i += NT) { nthr_s[i] = -thr[q0 + i]; invq_s[i] = invq[q0 + i]; cnt_s[i] = 0; }
+    for (int i = tid; i < QT; i += NT) {
+        const float th = thr[q0 + i];
+        const uint16_t hi = enc16(th), lo = enc16(th - dec16(hi));
+        thp_s[i] = hi | ((uint32_t)lo << 16);
+        invq_s[i] = invq[q0 + i];
+        cnt_s[i] = 0;
+    }
     if (tid == 0) *total_s = 0;
 
-    // Accumulators: never zeroed explicitly -- the first MFMA of a tile takes a zero C operand.
+    // Accumulators: (re)initialised at the start of every tile by MFMAs with a zero C operand.
     // (An explicit re-zeroing inside the tile loop makes the compiler keep two copies of them.)
     f32x16_t acc[MQ][MR];
 
@@ -184,8 +193,7 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
     };
     // `mid` (the LDS stores of the next step's operands) runs between the second and third k-step, so
     // that those stores overlap the MFMAs instead of forming a separate period before the barrier.
-    auto compute = [&](int s, auto first_c, auto mid) __attribute__((always_inline)) {
-        constexpr bool FIRST = decltype(first_c)::value;
+    auto compute = [&](int s, auto mid) __attribute__((always_inline)) {
         if constexpr (DT == 0) {
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) {
@@ -198,8 +206,7 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
                 for (int a = 0; a < MQ; ++a)
 #pragma unroll
                     for (int b = 0; b < MR; ++b) {
-                        if (FIRST && ks == 0) { f32x16_t z = {0.f}; acc[a][b] = mfma32<1>(al[a], bh[b], z); }
-                        else acc[a][b] = mfma32<1>(al[a], bh[b], acc[a][b]);
+                        acc[a][b] = mfma32<1>(al[a], bh[b], acc[a][b]);
                         acc[a][b] = mfma32<1>(ah[a], bl[b], acc[a][b]);
                         acc[a][b] = mfma32<1>(ah[a], bh[b], acc[a][b]);
                     }
@@ -230,8 +237,7 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
                 for (int a = 0; a < MQ; ++a)
 #pragma unroll
                     for (int b = 0; b < MR; ++b) {
-                        if (FIRST && ks == 0) { f32x16_t z = {0.f}; acc[a][b] = mfma32<DT>(af[0][a], bf[0][b], z); }
-                        else acc[a][b] = mfma32<DT>(af[ks & FB][a], bf[ks & FB][b], acc[a][b]);
+                        acc[a][b] = mfma32<DT>(af[ks & FB][a], bf[ks & FB][b], acc[a][b]);
                     }
                 __builtin_amdgcn_sched_barrier(0);
                 if (ks == 1) { mid(); __builtin_amdgcn_sched_barrier(0); }
@@ -271,15 +277,49 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
         __syncthreads();
     };
 
-    // Inverse norms of this lane's MR bank rows of the current tile; loaded when the tile starts so
-    // that they have arrived long before the epilogue needs them.
-    float inv_r[MR];
+    // Inverse norms of this lane's MR bank rows: inv_r for the current tile, inv_n for the next one
+    // (loaded a whole tile ahead, so they have long arrived when a tile starts).
+    float inv_r[MR], inv_n[MR];
     auto load_invnorm = [&](int ti) __attribute__((always_inline)) {
-        const int64_t t = level_tile(L, first_j + ti * stride_j);
+        const int64_t t = level_tile(L, first_j + (ti < my_tiles ? ti : my_tiles - 1) * stride_j);
 #pragma unroll
         for (int b = 0; b < MR; ++b) {
             int64_t id = t * TILE_ROWS + (wr * MR + b) * 32 + l32;
-            inv_r[b] = invnorm[id < N ? id : N - 1];
+            inv_n[b] = invnorm[id < N ? id : N - 1];
+        }
+    };
+
+    // Start of a tile.  The accumulators are not zeroed but initialised, by one MFMA per 32x32 block,
+    // with  - threshold[query] * norm[row] : the filter  score * invnorm >= threshold  is
+    // score - threshold * norm >= 0, so after the k-loop the epilogue only has to look at signs.
+    // The operands are a 3-term extension, query side (th, th, tl), bank side -(nh, nl, nh), with
+    // threshold = th + tl and norm = nh + nl in the operands' 16-bit type (the dropped tl*nl term and
+    // the residuals are ~2^-16 relative, inside the margin).  The sparsest pass has no threshold: its
+    // query-side extension is zero and the accumulators start at zero.
+    auto tile_init = [&](int ti) __attribute__((always_inline)) {
+#pragma unroll
+        for (int b = 0; b < MR; ++b) inv_r[b] = inv_n[b];
+        load_invnorm(ti + 1);
+        uint32_t bx[MR], by[MR];
+#pragma unroll
+        for (int b = 0; b < MR; ++b) {
+            const float norm = 1.0f / inv_r[b];
+            const uint16_t nh = enc16(norm), nl = enc16(norm - dec16(nh));
+            const uint32_t mh = nh ^ 0x8000u, ml = nl ^ 0x8000u;
+            bx[b] = half ? 0u : (mh | (ml << 16));
+            by[b] = half ? 0u : mh;
+        }
+        const bool use_thr = L.rho != 0;
+#pragma unroll
+        for (int a = 0; a < MQ; ++a) {
+            const uint32_t tp = use_thr ? thp_s[(wq * MQ + a) * 32 + l32] : 0u;
+            const u32x4_t aext = {half ? 0u : ((tp & 0xffffu) | (tp << 16)), half ? 0u : (tp >> 16), 0u, 0u};
+#pragma unroll
+            for (int b = 0; b < MR; ++b) {
+                const u32x4_t bext = {bx[b], by[b], 0u, 0u};
+                const f32x16_t z = {0.f};
+                acc[a][b] = mfma32<DT == 0 ? 1 : DT>(aext, bext, z);
+            }
         }
     };
 
@@ -320,36 +360,36 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
             // Filter against the per-query thresholds.  Survivors (rare) go to a workgroup list in
             // LDS first, so that the global slot counters are bumped once per (workgroup, query)
             // and all at the same time, instead of one dependent device-wide atomic per survivor.
-            // Pass 1, every score: d = score * invnorm - threshold (one FMA against the negated
-            // threshold kept in LDS), and the largest d of each 32x32 block (max3).  Only where that
-            // is >= 0 does a lane build the block's 16-bit survivor mask, from the sign bits of d.
+            // The accumulators hold  score - threshold * norm  (see tile_init): survivors are the
+            // non-negative values.
+            // Pass 1.  Float bit patterns compared as signed integers: negative floats are
+            // negative integers, so "some value >= +0" is "integer max >= 0" (max3, no NaN handling).
             uint32_t msk[MQ * MR];
             uint32_t mine = 0;
 #pragma unroll
             for (int b = 0; b < MR; ++b) {
                 int opaque = 0;
                 asm volatile("" : "+v"(opaque));
-                const int half = (lane >> 5) + opaque, l32 = (lane & 31) + opaque;
-                const bool valid = t * TILE_ROWS + (wr * MR + b) * 32 + l32 < N;
-                const float inve = inv_r[b];
+                const bool valid = t * TILE_ROWS + (wr * MR + b) * 32 + (lane & 31) + opaque < N;
 #pragma unroll
                 for (int a = 0; a < MQ; ++a) {
-                    const int qb = (wq * MQ + a) * 32 + 4 * half;     // local query of register 0
-                    float d[16];
+                    int mx = max((int)__float_as_uint(acc[a][b][0]), (int)__float_as_uint(acc[a][b][1]));
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) d[r] = fmaf(acc[a][b][r], inve, nthr_s[qb + 8 * (r >> 2) + (r & 3)]);
-                    float mx = fmaxf(d[0], d[1]);
-#pragma unroll
-                    for (int r = 2; r < 16; r += 2) mx = fmaxf(mx, fmaxf(d[r], d[r + 1]));
+                    for (int r = 2; r < 16; r += 2)
+                        mx = max(mx, max((int)__float_as_uint(acc[a][b][r]), (int)__float_as_uint(acc[a][b][r + 1])));
+                    const bool hit = valid && mx >= 0;
                     uint32_t m = 0;
-                    if (valid && mx >= 0.f) {
+                    if (__builtin_amdgcn_ballot_w64(hit) != 0) {      // most blocks have no hit at all
+                        uint32_t neg = 0;                                // sign bits, register 15 first
+                        asm volatile("" : "+v"(neg));                   // keeps this a real branch
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) m |= ((~__float_as_uint(d[r])) >> 31) << r;
+                        for (int r = 15; r >= 0; --r) neg = __builtin_amdgcn_alignbit(neg, __float_as_uint(acc[a][b][r]), 31);
+                        m = hit ? (~neg & 0xffffu) : 0u;
                     }
                     msk[a * MR + b] = m;
                     mine += __popc(m);
-                    __builtin_amdgcn_sched_barrier(0);
                 }
+                __builtin_amdgcn_sched_barrier(0);
             }
             // Slots: one LDS atomic per wavefront and tile (prefix sum of the lanes' counts).
             uint32_t incl = mine;
@@ -368,6 +408,8 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
                     const int half = (lane >> 5) + opaque, l32 = (lane & 31) + opaque;
                     const int32_t id = (int32_t)(t * TILE_ROWS + (wr * MR + b) * 32 + l32);
                     const float inve = inv_r[b];
+                    const float norm = 1.0f / inve;
+                    const float nh_v = dec16(enc16(norm)), nl_v = dec16(enc16(norm - nh_v));
 #pragma unroll
                     for (int a = 0; a < MQ; ++a) {
                         const uint32_t m = msk[a * MR + b];
@@ -377,7 +419,10 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
                             for (int r = 0; r < 16; ++r)
                                 if (m & (1u << r)) {
                                     const int ql = qb + 8 * (r >> 2) + (r & 3);
-                                    const uint64_t key = pack_key(acc[a][b][r] * inve * invq_s[ql], id);
+                                    const uint32_t tp = thp_s[ql];
+                                    const float th = dec16((uint16_t)(tp & 0xffffu)), tl = dec16((uint16_t)(tp >> 16));
+                                    const float dot = acc[a][b][r] + (th * nh_v + th * nl_v + tl * nh_v);
+                                    const uint64_t key = pack_key(dot * inve * invq_s[ql], id);
                                     if (slot < (uint32_t)SCAN_LIST_CAP) { lkey[slot] = key; lq[slot] = (uint32_t)ql; }
                                     else {   // list full (a very loose threshold): fall back to the direct path
                                         uint32_t pos = atomicAdd(cnt + q0 + ql, 1u);
@@ -398,13 +443,12 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
     };
 
     // ---- pipeline over the flattened (tile, k-block) sequence; g counts steps over all tiles ----
-    auto phase = [&](int s, u32x4_t (&ld_b)[BCH], u32x4_t (&ld_q)[QCH], u32x4_t (&st_b)[BCH], u32x4_t (&st_q)[QCH],
-                     auto first_c) __attribute__((always_inline)) {
+    auto phase = [&](int s, u32x4_t (&ld_b)[BCH], u32x4_t (&ld_q)[QCH], u32x4_t (&st_b)[BCH], u32x4_t (&st_q)[QCH]) __attribute__((always_inline)) {
         // LDS stage s holds the current step; registers st_b hold the bank block of the next one;
         // ld_b is free for the one after that
         gload_q(ld_q);
         gload(ld_b);
-        compute(s, first_c, [&]() __attribute__((always_inline)) { lstore(s ^ 1, st_b, st_q); });
+        compute(s, [&]() __attribute__((always_inline)) { lstore(s ^ 1, st_b, st_q); });
         __syncthreads();
     };
     gload(gbA);
@@ -413,13 +457,12 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
     gload_q(gqB);
     lstore(0, gbA, gqA);
     __syncthreads();
+    load_invnorm(0);
     for (int ti = 0; ti < my_tiles; ++ti) {
-        load_invnorm(ti);
-        phase(0, gbA, gqA, gbB, gqB, std::true_type{});
-        phase(1, gbB, gqB, gbA, gqA, std::false_type{});
-        for (int st = 2; st < nsteps; st += 2) {
-            phase(0, gbA, gqA, gbB, gqB, std::false_type{});
-            phase(1, gbB, gqB, gbA, gqA, std::false_type{});
+        tile_init(ti);
+        for (int st = 0; st < nsteps; st += 2) {
+            phase(0, gbA, gqA, gbB, gqB);
+            phase(1, gbB, gqB, gbA, gqA);
         }
         epilogue(ti);
     }

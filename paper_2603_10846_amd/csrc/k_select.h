@@ -43,7 +43,7 @@ __global__ __launch_bounds__(1024) void k_select(uint64_t* __restrict__ surv, ui
     const int n = raw > (uint32_t)SURV_CAP ? SURV_CAP : (int)raw;
     if (raw > (uint32_t)SURV_CAP && tid == 0) atomicAdd(counters + 1, 1u);
     if (n < k1) {                       // fewer rows than the pool size: keep them all, no threshold
-        if (tid == 0) { cnt[b] = (uint32_t)n; thr[b] = -INFINITY; }
+        if (tid == 0) { cnt[b] = (uint32_t)n; thr[b] = -2.0f / invq[b]; }   // finite floor, see k_prep_queries
         return;
     }
     uint64_t key[8];
