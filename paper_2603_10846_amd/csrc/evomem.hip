@@ -382,16 +382,16 @@ extern "C" int mem_retrieve(evomem_t* h, const float* queries_dev, int B, int st
             hipLaunchKernelGGL(k_select, dim3(B), dim3(1024), 0, st, surv, cnt, thr, (const float*)invq, counters, k1, margin);
             LAUNCHCHK();
         }
-        dim3 rgrid((unsigned)(KEEP_MAX / 4), (unsigned)B);
+        dim3 rgrid((unsigned)B);
         if (h->dtype == MEM_F32)
-            hipLaunchKernelGGL(k_rescore<0>, rgrid, dim3(256), 0, st, (const void*)h->store, (const float*)qf, (const double*)invq64, (const uint64_t*)surv, (const uint32_t*)cnt, exact, h->nkb);
+            hipLaunchKernelGGL(k_rescore<0>, rgrid, dim3(1024), 0, st, (const void*)h->store, (const float*)qf, (const double*)invq64, (const uint64_t*)surv, (const uint32_t*)cnt, exact, h->nkb);
         else if (h->dtype == MEM_BF16)
-            hipLaunchKernelGGL(k_rescore<1>, rgrid, dim3(256), 0, st, (const void*)h->store, (const float*)qf, (const double*)invq64, (const uint64_t*)surv, (const uint32_t*)cnt, exact, h->nkb);
+            hipLaunchKernelGGL(k_rescore<1>, rgrid, dim3(1024), 0, st, (const void*)h->store, (const float*)qf, (const double*)invq64, (const uint64_t*)surv, (const uint32_t*)cnt, exact, h->nkb);
         else
-            hipLaunchKernelGGL(k_rescore<2>, rgrid, dim3(256), 0, st, (const void*)h->store, (const float*)qf, (const double*)invq64, (const uint64_t*)surv, (const uint32_t*)cnt, exact, h->nkb);
+            hipLaunchKernelGGL(k_rescore<2>, rgrid, dim3(1024), 0, st, (const void*)h->store, (const float*)qf, (const double*)invq64, (const uint64_t*)surv, (const uint32_t*)cnt, exact, h->nkb);
         LAUNCHCHK();
     }
-    hipLaunchKernelGGL(k_rerank, dim3(B), dim3(256), 0, st, (const uint64_t*)surv, (const uint32_t*)cnt, (const double*)exact,
+    hipLaunchKernelGGL(k_rerank, dim3(B), dim3(RERANK_T), 0, st, (const uint64_t*)surv, (const uint32_t*)cnt, (const double*)exact,
                        (const float*)(h->q + (int64_t)stage * h->capacity), k1, k2, (double)lambda, out_ids_dev, out_scores_dev,
                        out_cand_ids_dev, out_cand_sims_dev);
     LAUNCHCHK();

@@ -6,10 +6,17 @@
 namespace evk {
 
 // In-LDS bitonic sort, descending, n a power of two, all threads of the workgroup take part.
+// Pair p of a stage belongs to thread p % nthreads, so a wavefront always works on the same
+// 128-element blocks; a stage with stride j <= 64 stays inside those blocks.  Hence a workgroup
+// barrier is needed only next to a stage with a larger stride -- between two small-stride stages
+// (and always in a one-wavefront workgroup) the wavefront's own in-order LDS accesses suffice.
 template <typename T, typename Less>
 __device__ __forceinline__ void bitonic_desc(T* a, int n, int tid, int nthreads, Less less) {
+    int prev_j = 1 << 30;                                     // "large": the caller's writes came from any thread
     for (int k = 2; k <= n; k <<= 1)
         for (int j = k >> 1; j > 0; j >>= 1) {
+            if (nthreads > 64 && (j > 64 || prev_j > 64)) __syncthreads();
+            else __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             for (int p = tid; p < (n >> 1); p += nthreads) {
                 int i = ((p & ~(j - 1)) << 1) | (p & (j - 1));   // index with bit j clear
                 int l = i | j;
@@ -17,8 +24,9 @@ __device__ __forceinline__ void bitonic_desc(T* a, int n, int tid, int nthreads,
                 T x = a[i], y = a[l];
                 if (less(x, y) == desc) { a[i] = y; a[l] = x; }
             }
-            __syncthreads();
+            prev_j = j;
         }
+    __syncthreads();
 }
 
 // After a scan pass, for one query: find the k1-th best survivor key (similarity desc, id asc) by
@@ -113,115 +121,145 @@ __global__ __launch_bounds__(1024) void k_select(uint64_t* __restrict__ surv, ui
 // stored row and accumulates dot product and squared norm in fp64 (products of 16-bit values are
 // exact, so this is the cosine of the stored vectors up to fp64 rounding).
 template <int DT>
-__global__ __launch_bounds__(256) void k_rescore(const void* __restrict__ store_, const float* __restrict__ qf,
-                                                 const double* __restrict__ invq64, const uint64_t* __restrict__ surv,
-                                                 const uint32_t* __restrict__ cnt, double* __restrict__ exact,
-                                                 int nkb) {
-    const int b = blockIdx.y, lane = threadIdx.x & 63;
-    const int j = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (j >= (int)cnt[b]) return;
-    const int32_t id = key_id(surv[(int64_t)b * SURV_CAP + j]);
+__global__ __launch_bounds__(1024) void k_rescore(const void* __restrict__ store_, const float* __restrict__ qf,
+                                                  const double* __restrict__ invq64, const uint64_t* __restrict__ surv,
+                                                  const uint32_t* __restrict__ cnt, double* __restrict__ exact,
+                                                  int nkb) {
+    // One workgroup per query; 16 lanes per candidate row, so a wavefront works on four rows at a
+    // time and every lane has up to eight 16-byte loads in flight.
+    const int b = blockIdx.x, sub = threadIdx.x & 15, grp = threadIdx.x >> 4;   // grp 0..63
+    const int n = (int)cnt[b];
     const float* q = qf + (int64_t)b * nkb * KB;
-    double dot = 0.0, ssq = 0.0;
-    if (DT == 0) {
-        const float* store = static_cast<const float*>(store_);
-        for (int c4 = lane; c4 < nkb * 16; c4 += 64) {
-            float4 x = *reinterpret_cast<const float4*>(store + off32(id, c4, nkb));
-            float4 y = *reinterpret_cast<const float4*>(q + c4 * 4);
-            dot += (double)x.x * y.x + (double)x.y * y.y + (double)x.z * y.z + (double)x.w * y.w;
-            ssq += (double)x.x * x.x + (double)x.y * x.y + (double)x.z * x.z + (double)x.w * x.w;
-        }
-    } else {
-        const uint16_t* store = static_cast<const uint16_t*>(store_);
-        for (int c8 = lane; c8 < nkb * 8; c8 += 64) {
-            uint4 pk = *reinterpret_cast<const uint4*>(store + off16(id, c8, nkb));
-            uint32_t w[4] = {pk.x, pk.y, pk.z, pk.w};
+    constexpr int EPC = DT == 0 ? 4 : 8;                 // elements per 16-byte chunk
+    const int nch = nkb * KB / EPC;                      // chunks per row
+    for (int j0 = 0; j0 < n; j0 += 64) {                 // uniform trip count: the shuffles below need all lanes
+        const int j = j0 + grp;
+        const bool live = j < n;
+        const int32_t id = live ? key_id(surv[(int64_t)b * SURV_CAP + j]) : 0;
+        double dot = 0.0, ssq = 0.0;
+        for (int c0 = sub; c0 < nch; c0 += 16 * 8) {
+            uint4 pk[8];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                uint16_t lo = (uint16_t)(w[i] & 0xffff), hi = (uint16_t)(w[i] >> 16);
-                double x0 = DT == 1 ? bf16_to_f(lo) : f16_to_f(lo);
-                double x1 = DT == 1 ? bf16_to_f(hi) : f16_to_f(hi);
-                dot += x0 * (double)q[c8 * 8 + 2 * i] + x1 * (double)q[c8 * 8 + 2 * i + 1];
-                ssq += x0 * x0 + x1 * x1;
+            for (int u = 0; u < 8; ++u) {
+                const int c = c0 + 16 * u;
+                pk[u] = make_uint4(0, 0, 0, 0);
+                if (live && c < nch) {
+                    if (DT == 0) pk[u] = *reinterpret_cast<const uint4*>(static_cast<const float*>(store_) + off32(id, c, nkb));
+                    else pk[u] = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(store_) + off16(id, c, nkb));
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int c = c0 + 16 * u;
+                if (c >= nch) break;
+                const uint32_t w[4] = {pk[u].x, pk[u].y, pk[u].z, pk[u].w};
+                if (DT == 0) {
+                    const float4 y = *reinterpret_cast<const float4*>(q + c * 4);
+                    const float yy[4] = {y.x, y.y, y.z, y.w};
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) { double x = __uint_as_float(w[i]); dot += x * (double)yy[i]; ssq += x * x; }
+                } else {
+                    const float4 y0 = *reinterpret_cast<const float4*>(q + c * 8), y1 = *reinterpret_cast<const float4*>(q + c * 8 + 4);
+                    const float yy[8] = {y0.x, y0.y, y0.z, y0.w, y1.x, y1.y, y1.z, y1.w};
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const uint16_t lo = (uint16_t)(w[i] & 0xffff), hi = (uint16_t)(w[i] >> 16);
+                        const double x0 = DT == 1 ? bf16_to_f(lo) : f16_to_f(lo);
+                        const double x1 = DT == 1 ? bf16_to_f(hi) : f16_to_f(hi);
+                        dot += x0 * (double)yy[2 * i] + x1 * (double)yy[2 * i + 1];
+                        ssq += x0 * x0 + x1 * x1;
+                    }
+                }
             }
         }
+#pragma unroll
+        for (int o = 8; o > 0; o >>= 1) { dot += __shfl_xor(dot, o, 64); ssq += __shfl_xor(ssq, o, 64); }
+        if (live && sub == 0) exact[(int64_t)b * KEEP_MAX + j] = dot * invq64[b] * (1.0 / sqrt(ssq));
     }
-    dot = wave_sum_d(dot);
-    ssq = wave_sum_d(ssq);
-    if (lane == 0) exact[(int64_t)b * KEEP_MAX + j] = dot * invq64[b] * (1.0 / sqrt(ssq));
 }
 
-struct SimId { double v; int32_t id; };
-__device__ __forceinline__ bool simid_less(const SimId& x, const SimId& y) {   // "x ranks below y"
-    return x.v < y.v || (x.v == y.v && x.id > y.id);
-}
+constexpr int RERANK_T = 256;
 
-// Deterministic sum of f(j), j < n, over a 256-thread workgroup (fixed tree).
-template <typename F>
-__device__ __forceinline__ double block_sum(double* red, int tid, int n, F f) {
-    double s = 0.0;
-    for (int j = tid; j < n; j += 256) s += f(j);
-    red[tid] = s;
+// Deterministic sum of one value per thread over a 256-thread workgroup: wavefront butterflies, then
+// the four partial sums added in a fixed order.
+__device__ __forceinline__ double block_sum(double* red, int tid, double x) {
+    x = wave_sum_d(x);
+    if ((tid & 63) == 0) red[tid >> 6] = x;
     __syncthreads();
-    for (int st = 128; st > 0; st >>= 1) { if (tid < st) red[tid] += red[tid + st]; __syncthreads(); }
-    double r = red[0];
+    double r = (red[0] + red[1]) + (red[2] + red[3]);
     __syncthreads();
     return r;
+}
+
+__device__ __forceinline__ bool ranks_before(double v, int32_t id, double w, int32_t jd) {   // (v,id) before (w,jd)?
+    return v > w || (v == w && id < jd);
 }
 
 // Candidate pool and value filter for one query (Sec. 3.2): order the re-scored candidates by
 // (similarity desc, id asc), keep k1 as the pool C(x); gather the stage's Q values; z-score both
 // over the pool (population deviation, denominator std + 1e-6); score = (1-lambda) z_s + lambda z_q;
 // emit the k2 best by (score desc, id asc).  All in fp64, scores rounded to fp32 on output.
-__global__ __launch_bounds__(256) void k_rerank(const uint64_t* __restrict__ surv, const uint32_t* __restrict__ cnt,
+// The lists are short (at most 512 and 256 entries), so both orderings are done by counting: every
+// thread counts how many entries precede its own (each step reads one LDS entry, broadcast to all
+// lanes) and writes its entry to that rank -- two barriers instead of a sorting network.
+__global__ __launch_bounds__(RERANK_T) void k_rerank(const uint64_t* __restrict__ surv, const uint32_t* __restrict__ cnt,
                                                 const double* __restrict__ exact, const float* __restrict__ qstage,
                                                 int k1, int k2, double lambda, int32_t* __restrict__ out_ids,
                                                 float* __restrict__ out_scores, int32_t* __restrict__ cand_ids,
                                                 float* __restrict__ cand_sims) {
-    __shared__ SimId a[KEEP_MAX];
-    __shared__ double qv[MEM_MAX_K1_INTERNAL];
-    __shared__ double red[256];
+    __shared__ double v0[KEEP_MAX], v1[MEM_MAX_K1_INTERNAL];
+    __shared__ int32_t i0[KEEP_MAX], i1[MEM_MAX_K1_INTERNAL];
+    __shared__ double red[4];
     const int b = blockIdx.x, tid = threadIdx.x;
     const int kk = (int)cnt[b];
-    for (int i = tid; i < KEEP_MAX; i += 256) {
-        SimId e;
-        if (i < kk) { e.v = exact[(int64_t)b * KEEP_MAX + i]; e.id = key_id(surv[(int64_t)b * SURV_CAP + i]); }
-        else        { e.v = -INFINITY; e.id = 0x7fffffff; }
-        a[i] = e;
+    for (int i = tid; i < kk; i += RERANK_T) {
+        v0[i] = exact[(int64_t)b * KEEP_MAX + i];
+        i0[i] = key_id(surv[(int64_t)b * SURV_CAP + i]);
     }
     __syncthreads();
-    bitonic_desc(a, KEEP_MAX, tid, 256, simid_less);
     const int k1e = kk < k1 ? kk : k1;
+    // ordering 1: the k1e best by (similarity desc, id asc) -> (v1, i1)
+    for (int i = tid; i < kk; i += RERANK_T) {
+        const double v = v0[i];
+        const int32_t id = i0[i];
+        int rank = 0;
+#pragma unroll 8
+        for (int j = 0; j < kk; ++j) rank += ranks_before(v0[j], i0[j], v, id);
+        if (rank < k1e) { v1[rank] = v; i1[rank] = id; }
+    }
+    __syncthreads();
     if (cand_ids)
-        for (int i = tid; i < k1; i += 256) {
-            cand_ids[(int64_t)b * k1 + i] = i < k1e ? a[i].id : -1;
-            cand_sims[(int64_t)b * k1 + i] = i < k1e ? (float)a[i].v : -INFINITY;
+        for (int i = tid; i < k1; i += RERANK_T) {
+            cand_ids[(int64_t)b * k1 + i] = i < k1e ? i1[i] : -1;
+            cand_sims[(int64_t)b * k1 + i] = i < k1e ? (float)v1[i] : -INFINITY;
         }
-    for (int i = tid; i < k1e; i += 256) qv[i] = (double)qstage[a[i].id];
-    __syncthreads();
-    double scale_s = 0.0, scale_q = 0.0, mean_s = 0.0, mean_q = 0.0;
-    if (k1e > 0) {
-        mean_s = block_sum(red, tid, k1e, [&](int j) { return a[j].v; }) / k1e;
-        mean_q = block_sum(red, tid, k1e, [&](int j) { return qv[j]; }) / k1e;
-        double var_s = block_sum(red, tid, k1e, [&](int j) { double x = a[j].v - mean_s; return x * x; }) / k1e;
-        double var_q = block_sum(red, tid, k1e, [&](int j) { double x = qv[j] - mean_q; return x * x; }) / k1e;
-        scale_s = 1.0 / (sqrt(var_s) + 1e-6);
-        scale_q = 1.0 / (sqrt(var_q) + 1e-6);
-    }
-    // scores overwrite the similarities of the pool; the rest of the array becomes padding
-    for (int i = tid; i < KEEP_MAX; i += 256) {
-        SimId e = a[i];
-        if (i < k1e) e.v = (1.0 - lambda) * ((e.v - mean_s) * scale_s) + lambda * ((qv[i] - mean_q) * scale_q);
-        else { e.v = -INFINITY; e.id = 0x7fffffff; }
-        a[i] = e;
+    // z-scores over the pool (one pool entry per thread, k1e <= 256)
+    const bool mine = tid < k1e;
+    const double sim = mine ? v1[tid] : 0.0;
+    const int32_t id = mine ? i1[tid] : 0x7fffffff;
+    const double qv = mine ? (double)qstage[id] : 0.0;
+    double score = -INFINITY;
+    if (k1e > 0) {                                                    // uniform
+        const double mean_s = block_sum(red, tid, sim) / k1e;
+        const double mean_q = block_sum(red, tid, qv) / k1e;
+        const double ds = mine ? sim - mean_s : 0.0, dq = mine ? qv - mean_q : 0.0;
+        const double var_s = block_sum(red, tid, ds * ds) / k1e;
+        const double var_q = block_sum(red, tid, dq * dq) / k1e;
+        const double scale_s = 1.0 / (sqrt(var_s) + 1e-6), scale_q = 1.0 / (sqrt(var_q) + 1e-6);
+        if (mine) score = (1.0 - lambda) * (ds * scale_s) + lambda * (dq * scale_q);
     }
     __syncthreads();
-    bitonic_desc(a, MEM_MAX_K1_INTERNAL, tid, 256, simid_less);
+    // ordering 2: the k2 best by (score desc, id asc); v0/i0 are reused for the scores
+    if (mine) { v0[tid] = score; i0[tid] = id; }
+    __syncthreads();
     const int k2e = k1e < k2 ? k1e : k2;
-    for (int i = tid; i < k2; i += 256) {
-        out_ids[(int64_t)b * k2 + i] = i < k2e ? a[i].id : -1;
-        out_scores[(int64_t)b * k2 + i] = i < k2e ? (float)a[i].v : -INFINITY;
+    if (mine) {
+        int rank = 0;
+#pragma unroll 8
+        for (int j = 0; j < k1e; ++j) rank += ranks_before(v0[j], i0[j], score, id);
+        if (rank < k2e) { out_ids[(int64_t)b * k2 + rank] = id; out_scores[(int64_t)b * k2 + rank] = (float)score; }
     }
+    for (int i = k2e + tid; i < k2; i += RERANK_T) { out_ids[(int64_t)b * k2 + i] = -1; out_scores[(int64_t)b * k2 + i] = -INFINITY; }
 }
 
 }  // namespace evk
