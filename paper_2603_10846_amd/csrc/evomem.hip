@@ -370,8 +370,12 @@ extern "C" int mem_retrieve(evomem_t* h, const float* queries_dev, int B, int st
             if (gemv) {
                 rc = B == 1 ? launch_gemv<1>(h, st, B, L) : B == 2 ? launch_gemv<2>(h, st, B, L) : launch_gemv<4>(h, st, B, L);
             } else {
-                rc = h->dtype == MEM_F32 ? launch_mfma_dt<0>(h, st, Bp, qt, L)
-                   : h->dtype == MEM_BF16 ? launch_mfma_dt<1>(h, st, Bp, qt, L) : launch_mfma_dt<2>(h, st, Bp, qt, L);
+                // a sparse pass has few bank tiles: give each workgroup fewer queries, so that more
+                // workgroups share the pass and each one's k-loop is shorter
+                int lqt = qt;
+                while (lqt > 32 && (int64_t)L.ntiles * (Bp / lqt) < 128) lqt >>= 1;
+                rc = h->dtype == MEM_F32 ? launch_mfma_dt<0>(h, st, Bp, lqt, L)
+                   : h->dtype == MEM_BF16 ? launch_mfma_dt<1>(h, st, Bp, lqt, L) : launch_mfma_dt<2>(h, st, Bp, lqt, L);
             }
             if (rc != MEM_OK) return rc;
             if (prof) {

@@ -135,10 +135,12 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
         for (int i = 0; i < QCH; ++i) gq[i] = *reinterpret_cast<const u32x4_t*>(qb + (i * NT + tid) * 8);
         if (++ldq_step == nsteps) ldq_step = 0;
     };
+    // first element of the bank tile the load cursor is on (recomputed only when the cursor moves on
+    // to another tile: level_tile() contains an integer division)
+    int64_t ld_tile_elem = level_tile(L, first_j) * nkb * (int64_t)BLOCK_ELEMS;
     auto gload = [&](u32x4_t (&gb)[BCH]) __attribute__((always_inline)) {
-        const int64_t t = level_tile(L, first_j + ld_ti * stride_j);
         if constexpr (DT == 0) {
-            const float* blk = static_cast<const float*>(store_) + (t * nkb + (rotated(ld_step) >> 1)) * (int64_t)BLOCK_ELEMS + (rotated(ld_step) & 1) * 32;
+            const float* blk = static_cast<const float*>(store_) + ld_tile_elem + (rotated(ld_step) >> 1) * (int64_t)BLOCK_ELEMS + (rotated(ld_step) & 1) * 32;
 #pragma unroll
             for (int i = 0; i < BCH; ++i) {
                 int g = i * NT + tid, r = g >> 3, c4 = g & 7;
@@ -146,13 +148,16 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
             }
         } else {
             const int kb = ld_step < real_steps ? rotated(ld_step) : real_steps - 1;
-            const uint16_t* blk = static_cast<const uint16_t*>(store_) + (t * nkb + kb) * (int64_t)BLOCK_ELEMS;
+            const uint16_t* blk = static_cast<const uint16_t*>(store_) + ld_tile_elem + kb * (int64_t)BLOCK_ELEMS;
 #pragma unroll
             for (int i = 0; i < BCH; ++i) gb[i] = *reinterpret_cast<const u32x4_t*>(blk + (i * NT + tid) * 8);
         }
         // past the last step the cursor stays on the last tile: the two loads issued there are never
         // consumed, but keeping every phase free of branches lets the loads stay in flight across it
-        if (++ld_step == nsteps) { ld_step = 0; if (ld_ti + 1 < my_tiles) ++ld_ti; }
+        if (++ld_step == nsteps) {
+            ld_step = 0;
+            if (ld_ti + 1 < my_tiles) { ++ld_ti; ld_tile_elem = level_tile(L, first_j + ld_ti * stride_j) * nkb * (int64_t)BLOCK_ELEMS; }
+        }
     };
     auto lstore = [&](int s, u32x4_t (&gb)[BCH], u32x4_t (&gq)[QCH]) __attribute__((always_inline)) {
         if constexpr (DT == 0) {
