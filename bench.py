@@ -28,7 +28,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="clustered", choices=["clustered", "mid", "large", "stream1m"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-queries", type=int, default=0, help="oracle sample size (0: 2 per thread)")
+    ap.add_argument("--cpu-queries", type=int, default=0, help="oracle sample size (0: 16 per thread, at most B)")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="only run a plain 1 GiB device-to-device copy five times (reference for HBM counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives); use --gpus 1")
@@ -39,6 +41,14 @@ def main():
 
     if not torch.cuda.is_available():
         sys.exit("bench.py: needs a GPU (there is no CPU path)")
+    if args.copy_probe:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")      # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_bytes_read": src.numel() * 4, "copy_probe_bytes_written": src.numel() * 4}))
+        return
     w = {"clustered": synth.CLUSTERED, "mid": synth.MID, "large": synth.LARGE,
          "stream1m": synth.scaled(synth.STREAM, N=1048576)}[args.workload]
     stage = synth.REFINE if args.workload == "large" else synth.DRAFT
@@ -123,7 +133,7 @@ def main():
     if not args.no_cpu_baseline:
         from oracle import oracle as orc
         threads = min(orc.max_threads(), 16)
-        nq = args.cpu_queries or 2 * threads
+        nq = min(w.B, args.cpu_queries or 16 * threads)
         dt = {"f32": 0, "bf16": 1, "f16": 2}[w.dtype]
         rounded = orc.round_to_store(host_rows, dt)
         del host_rows
