@@ -246,7 +246,7 @@ std::vector<Level> plan_levels(int64_t N, int k1) {
 }
 
 template <int DT, int MQ, int WQ, int MR, int WR>
-int launch_mfma(evomem* h, hipStream_t st, int Bp, const Level& L) {
+int launch_mfma(evomem* h, hipStream_t st, int Bp, const Level& L, int k1) {
     constexpr int QT = 32 * MQ * WQ;
     constexpr int lds = scan_mfma_lds_bytes<QT>();
     auto kern = k_scan_mfma<DT, MQ, WQ, MR, WR>;
@@ -265,21 +265,27 @@ int launch_mfma(evomem* h, hipStream_t st, int Bp, const Level& L) {
     if (groups < 1) groups = 1;
     if (groups > (L.ntiles + 7) / 8) groups = (L.ntiles + 7) / 8;
     dim3 grid((unsigned)(8 * nqt * groups)), block(64 * WQ * WR);
+    // A pass is expected to keep about k1 * rho rows per query; spread over its tiles that is the
+    // number of survivors a workgroup stages per tile, and it writes them out when half its list is used.
+    const double per_tile = L.rho ? (double)k1 * L.rho * QT / L.ntiles : 1.0;
+    int flush_every = (int)(SCAN_LIST_CAP / 2 / (per_tile + 1.0));
+    if (flush_every < 1) flush_every = 1;
+    if (flush_every > 64) flush_every = 64;
     unsigned char* ws = h->ws;
     hipLaunchKernelGGL(kern, grid, block, lds, st, (const void*)h->store, (const float*)h->invnorm,
                        (const uint16_t*)(ws + h->w.qop), (const float*)(ws + h->w.invq), (const float*)(ws + h->w.thr),
-                       (uint32_t*)(ws + h->w.cnt), (uint64_t*)(ws + h->w.surv), h->N, h->nkb, Bp, L);
+                       (uint32_t*)(ws + h->w.cnt), (uint64_t*)(ws + h->w.surv), h->N, h->nkb, Bp, L, flush_every);
     LAUNCHCHK();
     return MEM_OK;
 }
 
 template <int DT>
-int launch_mfma_dt(evomem* h, hipStream_t st, int Bp, int qt, const Level& L) {
+int launch_mfma_dt(evomem* h, hipStream_t st, int Bp, int qt, const Level& L, int k1) {
     switch (qt) {
-        case 32: return launch_mfma<DT, 1, 1, 2, 4>(h, st, Bp, L);
-        case 64: return launch_mfma<DT, 2, 1, 2, 4>(h, st, Bp, L);
-        case 128: return launch_mfma<DT, 2, 2, 4, 2>(h, st, Bp, L);
-        default: return launch_mfma<DT, 4, 2, 2, 4>(h, st, Bp, L);   // 8 wavefronts, 128 x 64 each
+        case 32: return launch_mfma<DT, 1, 1, 2, 4>(h, st, Bp, L, k1);
+        case 64: return launch_mfma<DT, 2, 1, 2, 4>(h, st, Bp, L, k1);
+        case 128: return launch_mfma<DT, 2, 2, 4, 2>(h, st, Bp, L, k1);
+        default: return launch_mfma<DT, 4, 2, 2, 4>(h, st, Bp, L, k1);   // 8 wavefronts, 128 x 64 each
     }
 }
 
@@ -374,8 +380,8 @@ extern "C" int mem_retrieve(evomem_t* h, const float* queries_dev, int B, int st
                 // workgroups share the pass and each one's k-loop is shorter
                 int lqt = qt;
                 while (lqt > 32 && (int64_t)L.ntiles * (Bp / lqt) < 128) lqt >>= 1;
-                rc = h->dtype == MEM_F32 ? launch_mfma_dt<0>(h, st, Bp, lqt, L)
-                   : h->dtype == MEM_BF16 ? launch_mfma_dt<1>(h, st, Bp, lqt, L) : launch_mfma_dt<2>(h, st, Bp, lqt, L);
+                rc = h->dtype == MEM_F32 ? launch_mfma_dt<0>(h, st, Bp, lqt, L, k1)
+                   : h->dtype == MEM_BF16 ? launch_mfma_dt<1>(h, st, Bp, lqt, L, k1) : launch_mfma_dt<2>(h, st, Bp, lqt, L, k1);
             }
             if (rc != MEM_OK) return rc;
             if (prof) {

@@ -45,6 +45,19 @@ __device__ __forceinline__ uint32_t pack_bf16x2_hi(float a, float b, float& ra, 
     return ha | ((uint32_t)hb << 16);
 }
 
+// Bitwise OR of a value over the 64 lanes of a wavefront, returned as a wavefront-uniform value:
+// shifts within rows of 16 lanes, then the row broadcasts, then lane 63 is read.
+__device__ __forceinline__ uint32_t wave_or(uint32_t x) {
+    int v = (int)x;
+    v |= __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);   // row_shr:1
+    v |= __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);   // row_shr:2
+    v |= __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);   // row_shr:4
+    v |= __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true);   // row_shr:8  -> lane 15 of each row
+    v |= __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, true);   // row_bcast:15 into rows 1 and 3
+    v |= __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, true);   // row_bcast:31 into rows 2 and 3
+    return (uint32_t)__builtin_amdgcn_readlane(v, 63);
+}
+
 constexpr int STAGE_BANK_BYTES = TILE_ROWS * 128;
 constexpr int SCAN_LIST_CAP = 2048;     // survivor entries a workgroup can stage per tile
 
@@ -61,7 +74,7 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
                                                    const uint16_t* __restrict__ qop, const float* __restrict__ invq,
                                                    const float* __restrict__ thr, uint32_t* __restrict__ cnt,
                                                    uint64_t* __restrict__ surv, int64_t N, int nkb, int Bp,
-                                                   Level L) {
+                                                   Level L, int flush_every) {
     static_assert((WQ * WR == 4 || WQ * WR == 8) && MR * WR == 8, "4 or 8 waves, 256 bank rows per workgroup");
     constexpr int NT = 64 * WQ * WR;                   // lanes per workgroup
     constexpr int QT = 32 * MQ * WQ;
@@ -396,16 +409,11 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
-            // Slots: one LDS atomic per wavefront and tile (prefix sum of the lanes' counts).
-            uint32_t incl = mine;
-#pragma unroll
-            for (int o = 1; o < 64; o <<= 1) { uint32_t up = __shfl_up(incl, o, 64); if (lane >= o) incl += up; }
-            const uint32_t wave_total = __shfl(incl, 63, 64);
-            if (wave_total) {                                   // uniform within the wavefront
-                uint32_t base = 0;
-                if (lane == 63) base = atomicAdd(total_s, wave_total);
-                uint32_t slot = __shfl(base, 63, 64) + incl - mine;
-                // Pass 2, survivors only.
+            // Slots: a lane with survivors reserves them with one LDS atomic.
+            if (__builtin_amdgcn_ballot_w64(mine != 0) != 0) {          // uniform within the wavefront
+                uint32_t slot = mine ? atomicAdd(total_s, mine) : 0u;
+                // Pass 2, survivors only.  Per block the union of the lanes' masks is brought into a
+                // scalar (DPP or-reduction), and only the registers named by its bits are visited.
 #pragma unroll
                 for (int b = 0; b < MR; ++b) {
                     int opaque = 0;
@@ -418,32 +426,46 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
 #pragma unroll
                     for (int a = 0; a < MQ; ++a) {
                         const uint32_t m = msk[a * MR + b];
-                        if (m) {
-                            const int qb = (wq * MQ + a) * 32 + 4 * half;
-#pragma unroll
-                            for (int r = 0; r < 16; ++r)
-                                if (m & (1u << r)) {
-                                    const int ql = qb + 8 * (r >> 2) + (r & 3);
-                                    const uint32_t tp = thp_s[ql];
-                                    const float th = dec16((uint16_t)(tp & 0xffffu)), tl = dec16((uint16_t)(tp >> 16));
-                                    const float dot = acc[a][b][r] + (th * nh_v + th * nl_v + tl * nh_v);
-                                    const uint64_t key = pack_key(dot * inve * invq_s[ql], id);
-                                    if (slot < (uint32_t)SCAN_LIST_CAP) { lkey[slot] = key; lq[slot] = (uint32_t)ql; }
-                                    else {   // list full (a very loose threshold): fall back to the direct path
-                                        uint32_t pos = atomicAdd(cnt + q0 + ql, 1u);
-                                        if (pos < (uint32_t)SURV_CAP) surv[(int64_t)(q0 + ql) * SURV_CAP + pos] = key;
-                                    }
-                                    ++slot;
+                        uint32_t wm = wave_or(m);                          // scalar
+                        const int qb = (wq * MQ + a) * 32 + 4 * half;
+                        while (wm) {
+                            const int r = __builtin_ctz(wm);
+                            wm &= wm - 1;
+                            float av;
+                            switch (r) {                                   // r is uniform: a scalar branch tree
+                                case 0: av = acc[a][b][0]; break;   case 1: av = acc[a][b][1]; break;
+                                case 2: av = acc[a][b][2]; break;   case 3: av = acc[a][b][3]; break;
+                                case 4: av = acc[a][b][4]; break;   case 5: av = acc[a][b][5]; break;
+                                case 6: av = acc[a][b][6]; break;   case 7: av = acc[a][b][7]; break;
+                                case 8: av = acc[a][b][8]; break;   case 9: av = acc[a][b][9]; break;
+                                case 10: av = acc[a][b][10]; break; case 11: av = acc[a][b][11]; break;
+                                case 12: av = acc[a][b][12]; break; case 13: av = acc[a][b][13]; break;
+                                case 14: av = acc[a][b][14]; break; default: av = acc[a][b][15]; break;
+                            }
+                            if (m & (1u << r)) {
+                                const int ql = qb + 8 * (r >> 2) + (r & 3);
+                                const uint32_t tp = thp_s[ql];
+                                const float th = dec16((uint16_t)(tp & 0xffffu)), tl = dec16((uint16_t)(tp >> 16));
+                                const float dot = av + (th * nh_v + th * nl_v + tl * nh_v);
+                                const uint64_t key = pack_key(dot * inve * invq_s[ql], id);
+                                if (slot < (uint32_t)SCAN_LIST_CAP) { lkey[slot] = key; lq[slot] = (uint32_t)ql; }
+                                else {   // list full (a very loose threshold): fall back to the direct path
+                                    uint32_t pos = atomicAdd(cnt + q0 + ql, 1u);
+                                    if (pos < (uint32_t)SURV_CAP) surv[(int64_t)(q0 + ql) * SURV_CAP + pos] = key;
                                 }
+                                ++slot;
+                            }
                         }
-                        __builtin_amdgcn_sched_barrier(0);
                     }
                 }
             }
-            // The list is carried from tile to tile and written out only when it is half full (and
-            // once at the end), so the device-wide round trip below is paid every few tiles.
-            __syncthreads();
-            if (*total_s >= (uint32_t)(SCAN_LIST_CAP / 2) || ti == my_tiles - 1) flush();   // uniform
+            // The list is carried from tile to tile and written out every `flush_every` tiles (the host
+            // sizes that from the expected number of survivors per tile; a surplus takes the direct
+            // path above) and once at the end, so the device-wide round trip is paid every few tiles.
+            if (ti % flush_every == flush_every - 1 || ti == my_tiles - 1) {     // uniform
+                __syncthreads();
+                flush();
+            }
         }
     };
 
