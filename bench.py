@@ -19,6 +19,24 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+COUNTER_SUMMARY = os.path.join(ROOT, "profiles", "k_scan_mfma_clustered_hbm_counters.txt")
+
+
+def measured_traffic(workload):
+    """HBM bytes per launch of the densest scan pass from the committed counter summary, or None when
+    it is for another workload or the kernel sources have changed since the counters were taken."""
+    import glob
+    import hashlib
+    if workload != "clustered" or not os.path.exists(COUNTER_SUMMARY):
+        return None
+    h = hashlib.sha256()
+    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2603_10846_amd", "csrc", "*"))):
+        h.update(os.path.basename(f).encode())
+        h.update(open(f, "rb").read())
+    fields = dict(l.split(": ", 1) for l in open(COUNTER_SUMMARY).read().splitlines() if ": " in l and " " not in l.split(": ")[0])
+    if fields.get("kernel_source_sha256") != h.hexdigest():
+        return None
+    return int(fields["traffic_bytes_per_launch"])
 
 
 def main():
@@ -123,9 +141,9 @@ def main():
     alg_bytes = dense_rows * w.d * elem
     achieved = alg_bytes / (avg_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": "k_scan_mfma (densest pass)", "achieved": round(achieved, 1),
-                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(args.workload),
                 "avg_launch_ms": round(avg_ms, 4), "launches": len(dense), "rows_per_launch": int(dense_rows),
-                "bytes_per_row": w.d * elem,
+                "bytes_per_row": w.d * elem, "algorithmic_bytes_per_launch": int(alg_bytes),
                 "mfma_tflops": round(2.0 * w.B * dense_rows * w.d / (avg_ms * 1e-3) / 1e12, 1),
                 "all_scan_passes_ms_per_step": round(sum(ms for ms, _ in prof) / steps, 4)}
 
