@@ -470,26 +470,31 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
     };
 
     // ---- pipeline over the flattened (tile, k-block) sequence; g counts steps over all tiles ----
-    auto phase = [&](int s, u32x4_t (&ld_b)[BCH], u32x4_t (&ld_q)[QCH], u32x4_t (&st_b)[BCH], u32x4_t (&st_q)[QCH]) __attribute__((always_inline)) {
-        // LDS stage s holds the current step; registers st_b hold the bank block of the next one;
-        // ld_b is free for the one after that
-        gload_q(ld_q);
-        gload(ld_b);
-        compute(s, [&]() __attribute__((always_inline)) { lstore(s ^ 1, st_b, st_q); });
+    auto phase = [&](int s, u32x4_t (&gb)[BCH], u32x4_t (&gq)[QCH]) __attribute__((always_inline)) {
+        // LDS stage s holds the current step; registers gb/gq hold the operands of the next one.  As
+        // soon as those are in LDS (half-way through the MFMAs) the same registers take the loads of
+        // the step three ahead, so two register sets are in flight at all times, tile epilogues included.
+        compute(s, [&]() __attribute__((always_inline)) {
+            lstore(s ^ 1, gb, gq);
+            gload_q(gq);
+            gload(gb);
+        });
         __syncthreads();
     };
-    gload(gbA);
     gload_q(gqA);
-    gload(gbB);
+    gload(gbA);
     gload_q(gqB);
+    gload(gbB);
     lstore(0, gbA, gqA);
+    gload_q(gqA);
+    gload(gbA);
     __syncthreads();
     load_invnorm(0);
     for (int ti = 0; ti < my_tiles; ++ti) {
         tile_init(ti);
         for (int st = 0; st < nsteps; st += 2) {
-            phase(0, gbA, gqA, gbB, gqB);
-            phase(1, gbB, gqB, gbA, gqA);
+            phase(0, gbB, gqB);
+            phase(1, gbA, gqA);
         }
         epilogue(ti);
     }
