@@ -45,17 +45,28 @@ __device__ __forceinline__ uint32_t pack_bf16x2_hi(float a, float b, float& ra, 
     return ha | ((uint32_t)hb << 16);
 }
 
-// Bitwise OR of a value over the 64 lanes of a wavefront, returned as a wavefront-uniform value:
-// shifts within rows of 16 lanes, then the row broadcasts, then lane 63 is read.
-__device__ __forceinline__ uint32_t wave_or(uint32_t x) {
+// Per-lane choice between two registers by a lane mask (one v_cndmask).  Written as an instruction
+// because the compiler turns the equivalent C++ selects over elements of an accumulator vector into
+// a dynamically indexed vector access, which it expands to a 16-way chain.  The two wait states
+// are the ones gfx950 needs between a vector compare writing the mask and a vector instruction
+// reading it; the compiler does not add them for instructions it cannot see.
+__device__ __forceinline__ float lane_select(float if_clear, float if_set, uint64_t lanes) {
+    float r;
+    asm("s_nop 1\n\tv_cndmask_b32_e64 %0, %1, %2, %3" : "=v"(r) : "v"(if_clear), "v"(if_set), "s"(lanes));
+    return r;
+}
+
+// Inclusive prefix sum over the 64 lanes of a wavefront (all lanes active): shifts within rows of 16
+// lanes, then the row broadcasts.  Lane 63 ends up with the total.
+__device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t x) {
     int v = (int)x;
-    v |= __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);   // row_shr:1
-    v |= __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);   // row_shr:2
-    v |= __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);   // row_shr:4
-    v |= __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true);   // row_shr:8  -> lane 15 of each row
-    v |= __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, true);   // row_bcast:15 into rows 1 and 3
-    v |= __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, true);   // row_bcast:31 into rows 2 and 3
-    return (uint32_t)__builtin_amdgcn_readlane(v, 63);
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);   // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);   // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);   // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true);   // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, true);   // row_bcast:15 into rows 1 and 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, true);   // row_bcast:31 into rows 2 and 3
+    return (uint32_t)v;
 }
 
 constexpr int STAGE_BANK_BYTES = TILE_ROWS * 128;
@@ -142,15 +153,33 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
         return k >= real_steps ? k - real_steps : k;
     };
     int ld_ti = 0, ld_step = 0, ldq_step = 0;
-    auto gload_q = [&](u32x4_t (&gq)[QCH]) __attribute__((always_inline)) {
+    // (the cursor step and the loads themselves are separate, so that the loads can be issued one
+    // at a time between MFMAs)
+    auto gnext_q = [&]() __attribute__((always_inline)) {
         const uint16_t* qb = qop + ((int64_t)rotated(ldq_step) * Bp + q0) * KB;
-#pragma unroll
-        for (int i = 0; i < QCH; ++i) gq[i] = *reinterpret_cast<const u32x4_t*>(qb + (i * NT + tid) * 8);
         if (++ldq_step == nsteps) ldq_step = 0;
+        return qb;
+    };
+    auto gpiece = [&](const uint16_t* base, int i) __attribute__((always_inline)) {
+        return *reinterpret_cast<const u32x4_t*>(base + (i * NT + tid) * 8);
+    };
+    auto gload_q = [&](u32x4_t (&gq)[QCH]) __attribute__((always_inline)) {
+        const uint16_t* qb = gnext_q();
+#pragma unroll
+        for (int i = 0; i < QCH; ++i) gq[i] = gpiece(qb, i);
     };
     // first element of the bank tile the load cursor is on (recomputed only when the cursor moves on
     // to another tile: level_tile() contains an integer division)
     int64_t ld_tile_elem = level_tile(L, first_j) * nkb * (int64_t)BLOCK_ELEMS;
+    auto gnext_b = [&]() __attribute__((always_inline)) {     // 16-bit stores only
+        const int kb = ld_step < real_steps ? rotated(ld_step) : real_steps - 1;
+        const uint16_t* blk = static_cast<const uint16_t*>(store_) + ld_tile_elem + kb * (int64_t)BLOCK_ELEMS;
+        if (++ld_step == nsteps) {
+            ld_step = 0;
+            if (ld_ti + 1 < my_tiles) { ++ld_ti; ld_tile_elem = level_tile(L, first_j + ld_ti * stride_j) * nkb * (int64_t)BLOCK_ELEMS; }
+        }
+        return blk;
+    };
     auto gload = [&](u32x4_t (&gb)[BCH]) __attribute__((always_inline)) {
         if constexpr (DT == 0) {
             const float* blk = static_cast<const float*>(store_) + ld_tile_elem + (rotated(ld_step) >> 1) * (int64_t)BLOCK_ELEMS + (rotated(ld_step) & 1) * 32;
@@ -159,17 +188,16 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
                 int g = i * NT + tid, r = g >> 3, c4 = g & 7;
                 gb[i] = *reinterpret_cast<const u32x4_t*>(blk + r * KB + c4 * 4);
             }
+            // past the last step the cursor stays on the last tile: the loads issued there are never
+            // consumed, but keeping every step free of branches lets the loads stay in flight across it
+            if (++ld_step == nsteps) {
+                ld_step = 0;
+                if (ld_ti + 1 < my_tiles) { ++ld_ti; ld_tile_elem = level_tile(L, first_j + ld_ti * stride_j) * nkb * (int64_t)BLOCK_ELEMS; }
+            }
         } else {
-            const int kb = ld_step < real_steps ? rotated(ld_step) : real_steps - 1;
-            const uint16_t* blk = static_cast<const uint16_t*>(store_) + ld_tile_elem + kb * (int64_t)BLOCK_ELEMS;
+            const uint16_t* blk = gnext_b();
 #pragma unroll
-            for (int i = 0; i < BCH; ++i) gb[i] = *reinterpret_cast<const u32x4_t*>(blk + (i * NT + tid) * 8);
-        }
-        // past the last step the cursor stays on the last tile: the two loads issued there are never
-        // consumed, but keeping every phase free of branches lets the loads stay in flight across it
-        if (++ld_step == nsteps) {
-            ld_step = 0;
-            if (ld_ti + 1 < my_tiles) { ++ld_ti; ld_tile_elem = level_tile(L, first_j + ld_ti * stride_j) * nkb * (int64_t)BLOCK_ELEMS; }
+            for (int i = 0; i < BCH; ++i) gb[i] = gpiece(blk, i);
         }
     };
     auto lstore = [&](int s, u32x4_t (&gb)[BCH], u32x4_t (&gq)[QCH]) __attribute__((always_inline)) {
@@ -197,21 +225,22 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
     };
     // Operand addresses.  Row (block*32 + l32) of an operand tile, logical chunk c = 2*k4 + half:
     // byte offset = block*4096 + l32*128 + ((c ^ f(l32)) * 16), the swizzle depending on l32 only.
-    // So four per-lane offsets per operand (k4 = 0..3, the wave's first block folded in) serve every
-    // block, both stages and all k-steps; the rest of the address is a compile-time constant.
+    // The k-step enters through bits 5..6 only, so the address for k-step k4 is the one for k-step 0
+    // with (k4 << 5) xor-ed in: one per-lane offset per operand (the wave's first block folded in)
+    // serves every block, both stages and all k-steps; the rest is a compile-time constant.
+    const uint32_t off0 = l32 * 128 + swz16(half, l32) * 16;
+    const uint32_t offA0 = off0 + STAGE_BANK_BYTES + wq * MQ * 4096, offB0 = off0 + wr * MR * 4096;
     uint32_t offA[4], offB[4];
 #pragma unroll
-    for (int k4 = 0; k4 < 4; ++k4) {
-        const uint32_t o = l32 * 128 + swz16(2 * k4 + half, l32) * 16;
-        offA[k4] = o + STAGE_BANK_BYTES + wq * MQ * 4096;
-        offB[k4] = o + wr * MR * 4096;
-    }
+    for (int k4 = 0; k4 < 4; ++k4) { offA[k4] = offA0 ^ (k4 << 5); offB[k4] = offB0 ^ (k4 << 5); }
     auto frag = [&](int s, uint32_t off, int block) __attribute__((always_inline)) {
         return *reinterpret_cast<const u32x4_t*>(smem + off + (s * STAGE_BYTES + block * 4096));
     };
-    // `mid` (the LDS stores of the next step's operands) runs between the second and third k-step, so
-    // that those stores overlap the MFMAs instead of forming a separate period before the barrier.
-    auto compute = [&](int s, auto mid) __attribute__((always_inline)) {
+    // One step: the MFMAs on LDS stage s, and meanwhile the operands of the next step (registers gb, gq,
+    // loaded two steps ago) go to stage s ^ 1 and the same registers take the loads of the step three
+    // ahead, so two register sets are in flight at all times, tile epilogues included.
+    u32x4_t af[MQ], bfr[2][MR];   // operand fragments of the 16-bit path, carried from step to step
+    auto compute = [&](int s, u32x4_t (&gb)[BCH], u32x4_t (&gq)[QCH], auto fetch_next) __attribute__((always_inline)) {
         if constexpr (DT == 0) {
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) {
@@ -229,41 +258,68 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
                         acc[a][b] = mfma32<1>(ah[a], bh[b], acc[a][b]);
                     }
                 __builtin_amdgcn_sched_barrier(0);
-                if (ks == 0) { mid(); __builtin_amdgcn_sched_barrier(0); }
+                if (ks == 0) {
+                    lstore(s ^ 1, gb, gq);
+                    gload_q(gq);
+                    gload(gb);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
         } else {
-            // Operand fragments are double buffered by hand (those of k-step ks+1 are read from LDS
-            // while the MFMAs of ks run) and the scheduler is fenced per k-step, which bounds the
-            // live fragment registers to two k-steps' worth.
-            // (With two wavefronts per SIMD the other wavefront's MFMAs cover the LDS latency, and the
-            // registers are better spent on loads in flight: fragments are then single buffered.)
-            constexpr int FB = NT == 512 ? 0 : 1;      // index mask of the fragment buffers
-            u32x4_t af[FB + 1][MQ], bf[FB + 1][MR];
-#pragma unroll
-            for (int a = 0; a < MQ; ++a) af[0][a] = frag(s, offA[0], a);
-#pragma unroll
-            for (int b = 0; b < MR; ++b) bf[0][b] = frag(s, offB[0], b);
+            // A software pipeline written out by hand, one slot per query block a of a k-step:
+            //   the MFMAs of block a (MR of them), then the LDS read of block a's fragment for the next
+            //   k-step into the registers those MFMAs have just read, then one piece of the side work.
+            // The bank fragments are used by every slot and are double buffered instead.  So every
+            // fragment is requested at least MR * (MQ - 1) MFMAs before its first use and a wavefront
+            // can keep the matrix pipe busy by itself; the LDS stores (k-steps 1 and 2) and the global
+            // loads (k-step 3) issue in the shadow of the MFMAs instead of forming a period without any.
+            // The scheduler is fenced per slot to keep this order (left alone it hoists the reads).
+            // On entry af and bfr[0] hold the fragments of k-step 0, fetched by the previous step or, for
+            // the first step of a tile, by the tile loop (the last step of a tile fetches nothing: the
+            // fragments would only occupy registers that the tile epilogue needs).
+            constexpr bool FETCH = decltype(fetch_next)::value;
+            const uint16_t* nq = gnext_q();
+            const uint16_t* nb = gnext_b();
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {
-                if (ks < 3 && FB) {
+                const int cur = ks & 1;
+                const uint32_t oa = offA0 ^ (((ks + 1) & 3) << 5), ob = offB0 ^ (((ks + 1) & 3) << 5);
+                // The step's only barrier: every wavefront has stored its share of stage s ^ 1 (k-steps
+                // 1 and 2) and has received all it reads from stage s (the fragments of k-step 3 were
+                // requested during k-step 2).  After it, k-step 3 still has its operands in registers,
+                // and its slots fetch the first fragments of the next step from stage s ^ 1, so the
+                // matrix pipe does not wait for LDS after the barrier.
+                if (ks == 3) __syncthreads();
+                if (ks < 3 || FETCH) {
 #pragma unroll
-                    for (int a = 0; a < MQ; ++a) af[(ks + 1) & FB][a] = frag(s, offA[ks + 1], a);
-#pragma unroll
-                    for (int b = 0; b < MR; ++b) bf[(ks + 1) & FB][b] = frag(s, offB[ks + 1], b);
+                    for (int b = 0; b < MR; ++b) bfr[cur ^ 1][b] = frag(ks < 3 ? s : s ^ 1, ob, b);
                 }
 #pragma unroll
-                for (int a = 0; a < MQ; ++a)
+                for (int a = 0; a < MQ; ++a) {
 #pragma unroll
-                    for (int b = 0; b < MR; ++b) {
-                        acc[a][b] = mfma32<DT>(af[ks & FB][a], bf[ks & FB][b], acc[a][b]);
+                    for (int b = 0; b < MR; ++b) acc[a][b] = mfma32<DT>(af[a], bfr[cur][b], acc[a][b]);
+                    if (ks < 3 || FETCH) af[a] = frag(ks < 3 ? s : s ^ 1, oa, a);
+                    if (ks == 1) {
+#pragma unroll
+                        for (int i = a * QCH / MQ; i < (a + 1) * QCH / MQ; ++i)
+                            *reinterpret_cast<u32x4_t*>(sq(s ^ 1) + (i * NT + tid) * 16) = gq[i];
                     }
-                __builtin_amdgcn_sched_barrier(0);
-                if (ks == 1) { mid(); __builtin_amdgcn_sched_barrier(0); }
-                if (ks < 3 && !FB) {
+                    if (ks == 2) {
 #pragma unroll
-                    for (int a = 0; a < MQ; ++a) af[0][a] = frag(s, offA[ks + 1], a);
+                        for (int i = a * BCH / MQ; i < (a + 1) * BCH / MQ; ++i)
+                            *reinterpret_cast<u32x4_t*>(sbank(s ^ 1) + (i * NT + tid) * 16) = gb[i];
+                    }
+                    // the registers stored during k-step 1 (query pieces) are reloaded during k-step 2,
+                    // those stored during k-step 2 (bank pieces) during k-step 3, a few per slot
+                    if (ks == 2) {
 #pragma unroll
-                    for (int b = 0; b < MR; ++b) bf[0][b] = frag(s, offB[ks + 1], b);
+                        for (int i = a * QCH / MQ; i < (a + 1) * QCH / MQ; ++i) gq[i] = gpiece(nq, i);
+                    }
+                    if (ks == 3) {
+#pragma unroll
+                        for (int i = a * BCH / MQ; i < (a + 1) * BCH / MQ; ++i) gb[i] = gpiece(nb, i);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
                 }
             }
         }
@@ -409,11 +465,16 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
-            // Slots: a lane with survivors reserves them with one LDS atomic.
+            // Slots: a prefix sum over the wavefront, one LDS atomic per wavefront for its total.
             if (__builtin_amdgcn_ballot_w64(mine != 0) != 0) {          // uniform within the wavefront
-                uint32_t slot = mine ? atomicAdd(total_s, mine) : 0u;
-                // Pass 2, survivors only.  Per block the union of the lanes' masks is brought into a
-                // scalar (DPP or-reduction), and only the registers named by its bits are visited.
+                const uint32_t incl = wave_inclusive_sum(mine);
+                uint32_t wave_base = 0;
+                if (lane == 63) wave_base = atomicAdd(total_s, incl);
+                uint32_t slot = (uint32_t)__builtin_amdgcn_readlane((int)wave_base, 63) + incl - mine;
+                // Pass 2, survivors only, all lanes in parallel: each lane takes the first set bit of its
+                // own mask, fetches that accumulator register with a two-level select (registers cannot
+                // be indexed per lane), and stages the key; the loop repeats while any lane of the
+                // wavefront has bits left (a lane seldom holds two survivors of one block).
 #pragma unroll
                 for (int b = 0; b < MR; ++b) {
                     int opaque = 0;
@@ -425,25 +486,23 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
                     const float nh_v = dec16(enc16(norm)), nl_v = dec16(enc16(norm - nh_v));
 #pragma unroll
                     for (int a = 0; a < MQ; ++a) {
-                        const uint32_t m = msk[a * MR + b];
-                        uint32_t wm = wave_or(m);                          // scalar
+                        uint32_t m = msk[a * MR + b];
                         const int qb = (wq * MQ + a) * 32 + 4 * half;
-                        while (wm) {
-                            const int r = __builtin_ctz(wm);
-                            wm &= wm - 1;
-                            float av;
-                            switch (r) {                                   // r is uniform: a scalar branch tree
-                                case 0: av = acc[a][b][0]; break;   case 1: av = acc[a][b][1]; break;
-                                case 2: av = acc[a][b][2]; break;   case 3: av = acc[a][b][3]; break;
-                                case 4: av = acc[a][b][4]; break;   case 5: av = acc[a][b][5]; break;
-                                case 6: av = acc[a][b][6]; break;   case 7: av = acc[a][b][7]; break;
-                                case 8: av = acc[a][b][8]; break;   case 9: av = acc[a][b][9]; break;
-                                case 10: av = acc[a][b][10]; break; case 11: av = acc[a][b][11]; break;
-                                case 12: av = acc[a][b][12]; break; case 13: av = acc[a][b][13]; break;
-                                case 14: av = acc[a][b][14]; break; default: av = acc[a][b][15]; break;
-                            }
-                            if (m & (1u << r)) {
-                                const int ql = qb + 8 * (r >> 2) + (r & 3);
+                        while (__builtin_amdgcn_ballot_w64(m != 0) != 0) {
+                            const int r = __builtin_ctz(m | 0x10000u);     // 16 for a lane without bits
+                            const int lo = r & 3, hi = (r >> 2) & 3;
+                            const uint64_t lo1 = __builtin_amdgcn_ballot_w64(lo == 1), lo3 = __builtin_amdgcn_ballot_w64(lo == 3);
+                            const uint64_t lo23 = __builtin_amdgcn_ballot_w64(lo >= 2);
+                            float g4[4];
+#pragma unroll
+                            for (int k = 0; k < 4; ++k)
+                                g4[k] = lane_select(lane_select(acc[a][b][4 * k], acc[a][b][4 * k + 1], lo1),
+                                                    lane_select(acc[a][b][4 * k + 2], acc[a][b][4 * k + 3], lo3), lo23);
+                            const float av = lane_select(lane_select(g4[0], g4[1], __builtin_amdgcn_ballot_w64(hi == 1)),
+                                                         lane_select(g4[2], g4[3], __builtin_amdgcn_ballot_w64(hi == 3)),
+                                                         __builtin_amdgcn_ballot_w64(hi >= 2));
+                            if (m) {
+                                const int ql = qb + 8 * hi + lo;
                                 const uint32_t tp = thp_s[ql];
                                 const float th = dec16((uint16_t)(tp & 0xffffu)), tl = dec16((uint16_t)(tp >> 16));
                                 const float dot = av + (th * nh_v + th * nl_v + tl * nh_v);
@@ -454,6 +513,7 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
                                     if (pos < (uint32_t)SURV_CAP) surv[(int64_t)(q0 + ql) * SURV_CAP + pos] = key;
                                 }
                                 ++slot;
+                                m &= m - 1;
                             }
                         }
                     }
@@ -470,16 +530,9 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
     };
 
     // ---- pipeline over the flattened (tile, k-block) sequence; g counts steps over all tiles ----
-    auto phase = [&](int s, u32x4_t (&gb)[BCH], u32x4_t (&gq)[QCH]) __attribute__((always_inline)) {
-        // LDS stage s holds the current step; registers gb/gq hold the operands of the next one.  As
-        // soon as those are in LDS (half-way through the MFMAs) the same registers take the loads of
-        // the step three ahead, so two register sets are in flight at all times, tile epilogues included.
-        compute(s, [&]() __attribute__((always_inline)) {
-            lstore(s ^ 1, gb, gq);
-            gload_q(gq);
-            gload(gb);
-        });
-        __syncthreads();
+    auto phase = [&](int s, u32x4_t (&gb)[BCH], u32x4_t (&gq)[QCH], auto fetch_next) __attribute__((always_inline)) {
+        compute(s, gb, gq, fetch_next);
+        if constexpr (DT == 0) __syncthreads();
     };
     gload_q(gqA);
     gload(gbA);
@@ -492,10 +545,18 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
     load_invnorm(0);
     for (int ti = 0; ti < my_tiles; ++ti) {
         tile_init(ti);
-        for (int st = 0; st < nsteps; st += 2) {
-            phase(0, gbB, gqB);
-            phase(1, gbA, gqA);
+        if constexpr (DT != 0) {
+#pragma unroll
+            for (int a = 0; a < MQ; ++a) af[a] = frag(0, offA0, a);
+#pragma unroll
+            for (int b = 0; b < MR; ++b) bfr[0][b] = frag(0, offB0, b);
         }
+        for (int st = 0; st < nsteps - 2; st += 2) {
+            phase(0, gbB, gqB, std::true_type{});
+            phase(1, gbA, gqA, std::true_type{});
+        }
+        phase(0, gbB, gqB, std::true_type{});
+        phase(1, gbA, gqA, std::false_type{});
         epilogue(ti);
     }
 }
