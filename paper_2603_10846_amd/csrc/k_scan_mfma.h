@@ -99,6 +99,17 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wq = wave / WR, wr = wave % WR;
     const int half = lane >> 5, l32 = lane & 31;
+    // Outside the k-loop (tile start, epilogue) lane coordinates are formed afresh: the wavefront's
+    // position from scalar registers, the lane index from the lane counter seeded with a zero the
+    // compiler cannot see through.  A per-lane value kept from the kernel's start would live on the
+    // stack across the k-loop (there is no register to spare), and the wait for its reload is a wait
+    // for every load in flight.
+    const int wq_u = __builtin_amdgcn_readfirstlane(wq), wr_u = __builtin_amdgcn_readfirstlane(wr);
+    auto fresh_lane = [&]() __attribute__((always_inline)) {
+        uint32_t z = 0;
+        asm volatile("" : "+v"(z));
+        return (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, z));
+    };
 
     // Workgroup -> (query tile, sequence of bank tiles).  Blocks are dealt to the 8 XCDs round-robin;
     // the nqt workgroups that share a bank tile are neighbours on one XCD and walk the tiles in the
@@ -239,6 +250,24 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
     // One step: the MFMAs on LDS stage s, and meanwhile the operands of the next step (registers gb, gq,
     // loaded two steps ago) go to stage s ^ 1 and the same registers take the loads of the step three
     // ahead, so two register sets are in flight at all times, tile epilogues included.
+    // Inverse norms of this lane's MR bank rows of the next tile.  They are requested in the last
+    // k-step of a tile (the fragment registers are free by then; across the whole k-loop there is
+    // no register to spare, and a value that gets spilled has to be waited for right after its
+    // request, which drains every load in flight) and turned into MFMA operands (tile_prepare)
+    // after that tile's epilogue, by when they have long arrived.  The rare epilogue paths that
+    // need an inverse norm of the current tile read it from memory again.
+    float inv_n[MR];
+    int tile_now = 0;
+    auto load_invnorm = [&](int ti) __attribute__((always_inline)) {
+        const int64_t t = level_tile(L, first_j + (ti < my_tiles ? ti : my_tiles - 1) * stride_j);
+        const int row0 = (wr_u * MR) * 32 + (fresh_lane() & 31);
+#pragma unroll
+        for (int b = 0; b < MR; ++b) {
+            const int64_t id = t * TILE_ROWS + row0 + b * 32;
+            inv_n[b] = invnorm[id < N ? id : N - 1];
+        }
+    };
+
     u32x4_t af[MQ], bfr[2][MR];   // operand fragments of the 16-bit path, carried from step to step
     auto compute = [&](int s, u32x4_t (&gb)[BCH], u32x4_t (&gq)[QCH], auto fetch_next) __attribute__((always_inline)) {
         if constexpr (DT == 0) {
@@ -318,11 +347,23 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
                     if (ks == 3) {
 #pragma unroll
                         for (int i = a * BCH / MQ; i < (a + 1) * BCH / MQ; ++i) gb[i] = gpiece(nb, i);
+                        if (!FETCH && a == MQ - 1) load_invnorm(tile_now + 1);
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
         }
+    };
+
+    // Key of a survivor from its accumulator value (score - threshold * norm, see tile_init): the
+    // threshold term is added back exactly as the MFMA formed it, then the cosine is taken.
+    auto finish_key = [&](float av, int ql, int32_t id, float inv) __attribute__((always_inline)) {
+        const float norm = __builtin_amdgcn_rcpf(inv);
+        const float nh = dec16(enc16(norm)), nl = dec16(enc16(norm - nh));
+        const uint32_t tp = thp_s[ql];
+        const float th = dec16((uint16_t)(tp & 0xffffu)), tl = dec16((uint16_t)(tp >> 16));
+        const float dot = av + (th * nh + th * nl + tl * nh);
+        return pack_key(dot * inv * invq_s[ql], id);
     };
 
     // Write the workgroup's staged survivors to the per-query lists (all lanes call it together):
@@ -344,23 +385,14 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
         for (uint32_t e = tid; e < total; e += NT) {
             uint32_t ql = lq[e] & 0xffffu, rank = lq[e] >> 16;
             uint32_t pos = base_s[ql] + rank;
-            if (pos < (uint32_t)SURV_CAP) surv[(int64_t)(q0 + ql) * SURV_CAP + pos] = lkey[e];
+            if (pos < (uint32_t)SURV_CAP) {
+                const int32_t id = (int32_t)(uint32_t)lkey[e];
+                surv[(int64_t)(q0 + ql) * SURV_CAP + pos] = finish_key(__uint_as_float((uint32_t)(lkey[e] >> 32)), (int)ql, id, invnorm[id]);
+            }
         }
         __syncthreads();
         if (tid == 0) *total_s = 0;
         __syncthreads();
-    };
-
-    // Inverse norms of this lane's MR bank rows: inv_r for the current tile, inv_n for the next one
-    // (loaded a whole tile ahead, so they have long arrived when a tile starts).
-    float inv_r[MR], inv_n[MR];
-    auto load_invnorm = [&](int ti) __attribute__((always_inline)) {
-        const int64_t t = level_tile(L, first_j + (ti < my_tiles ? ti : my_tiles - 1) * stride_j);
-#pragma unroll
-        for (int b = 0; b < MR; ++b) {
-            int64_t id = t * TILE_ROWS + (wr * MR + b) * 32 + l32;
-            inv_n[b] = invnorm[id < N ? id : N - 1];
-        }
     };
 
     // Start of a tile.  The accumulators are not zeroed but initialised, by one MFMA per 32x32 block,
@@ -370,23 +402,25 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
     // threshold = th + tl and norm = nh + nl in the operands' 16-bit type (the dropped tl*nl term and
     // the residuals are ~2^-16 relative, inside the margin).  The sparsest pass has no threshold: its
     // query-side extension is zero and the accumulators start at zero.
-    auto tile_init = [&](int ti) __attribute__((always_inline)) {
-#pragma unroll
-        for (int b = 0; b < MR; ++b) inv_r[b] = inv_n[b];
-        load_invnorm(ti + 1);
-        uint32_t bx[MR], by[MR];
+    // Norm operands of the tile about to start, from the inverse norms requested a tile earlier.
+    uint32_t bx[MR], by[MR];
+    auto tile_prepare = [&]() __attribute__((always_inline)) {
+        const int half = fresh_lane() >> 5;
 #pragma unroll
         for (int b = 0; b < MR; ++b) {
-            const float norm = 1.0f / inv_r[b];
+            const float norm = __builtin_amdgcn_rcpf(inv_n[b]);   // finish_key() forms it the same way
             const uint16_t nh = enc16(norm), nl = enc16(norm - dec16(nh));
             const uint32_t mh = nh ^ 0x8000u, ml = nl ^ 0x8000u;
             bx[b] = half ? 0u : (mh | (ml << 16));
             by[b] = half ? 0u : mh;
         }
+    };
+    auto tile_init = [&](int ti) __attribute__((always_inline)) {
         const bool use_thr = L.rho != 0;
+        const int ln = fresh_lane(), half = ln >> 5, l32 = ln & 31;
 #pragma unroll
         for (int a = 0; a < MQ; ++a) {
-            const uint32_t tp = use_thr ? thp_s[(wq * MQ + a) * 32 + l32] : 0u;
+            const uint32_t tp = use_thr ? thp_s[(wq_u * MQ + a) * 32 + l32] : 0u;
             const u32x4_t aext = {half ? 0u : ((tp & 0xffffu) | (tp << 16)), half ? 0u : (tp >> 16), 0u, 0u};
 #pragma unroll
             for (int b = 0; b < MR; ++b) {
@@ -401,21 +435,16 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
     auto epilogue = [&](int ti) __attribute__((always_inline)) {
         const int j = first_j + ti * stride_j;
         const int64_t t = level_tile(L, j);
-        // The lane coordinates are re-derived from an opaque zero, so that the many per-lane output
-        // addresses below are computed here, once per tile, instead of being hoisted out of the
-        // k-loop and kept (spilled) across it.
         if (L.rho == 0) {
             // Sparsest pass: no threshold yet, every row is kept.  Slot = position of the row in
             // this pass, so no counter is needed (the count was preset to the pass's valid rows).
 #pragma unroll
             for (int b = 0; b < MR; ++b) {
-                int opaque = 0;
-                asm volatile("" : "+v"(opaque));
-                const int half = (lane >> 5) + opaque, l32 = (lane & 31) + opaque;
-                const int rt = (wr * MR + b) * 32 + l32;
+                const int ln = fresh_lane(), half = ln >> 5, l32 = ln & 31;
+                const int rt = (wr_u * MR + b) * 32 + l32;
                 const int64_t id = t * TILE_ROWS + rt;
                 if (id < N) {
-                    const float inve = inv_r[b];
+                    const float inve = invnorm[id];
                     const int64_t pos = (int64_t)j * TILE_ROWS + rt;
 #pragma unroll
                     for (int a = 0; a < MQ; ++a) {
@@ -423,7 +452,7 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
                         asm volatile("" : "+v"(opq));
 #pragma unroll
                         for (int r = 0; r < 16; ++r) {
-                            const int ql = (wq * MQ + a) * 32 + 4 * (half + opq) + 8 * (r >> 2) + (r & 3);
+                            const int ql = (wq_u * MQ + a) * 32 + 4 * (half + opq) + 8 * (r >> 2) + (r & 3);
                             surv[(int64_t)(q0 + ql) * SURV_CAP + pos] = pack_key(acc[a][b][r] * inve * invq_s[ql], (int32_t)id);
                         }
                         __builtin_amdgcn_sched_barrier(0);
@@ -436,30 +465,20 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
             // and all at the same time, instead of one dependent device-wide atomic per survivor.
             // The accumulators hold  score - threshold * norm  (see tile_init): survivors are the
             // non-negative values.
-            // Pass 1.  Float bit patterns compared as signed integers: negative floats are
-            // negative integers, so "some value >= +0" is "integer max >= 0" (max3, no NaN handling).
+            // Pass 1.  Per block and lane a 16-bit mask of the non-negative accumulators, built from the
+            // sign bits with one funnel shift per register (no test for "no survivor in this block"
+            // first: at the survivor rates of the dense passes nearly every block has some).
             uint32_t msk[MQ * MR];
             uint32_t mine = 0;
 #pragma unroll
             for (int b = 0; b < MR; ++b) {
-                int opaque = 0;
-                asm volatile("" : "+v"(opaque));
-                const bool valid = t * TILE_ROWS + (wr * MR + b) * 32 + (lane & 31) + opaque < N;
+                const bool valid = t * TILE_ROWS + (wr_u * MR + b) * 32 + (fresh_lane() & 31) < N;
 #pragma unroll
                 for (int a = 0; a < MQ; ++a) {
-                    int mx = max((int)__float_as_uint(acc[a][b][0]), (int)__float_as_uint(acc[a][b][1]));
+                    uint32_t neg = 0;                                    // sign bits, register 15 first
 #pragma unroll
-                    for (int r = 2; r < 16; r += 2)
-                        mx = max(mx, max((int)__float_as_uint(acc[a][b][r]), (int)__float_as_uint(acc[a][b][r + 1])));
-                    const bool hit = valid && mx >= 0;
-                    uint32_t m = 0;
-                    if (__builtin_amdgcn_ballot_w64(hit) != 0) {      // most blocks have no hit at all
-                        uint32_t neg = 0;                                // sign bits, register 15 first
-                        asm volatile("" : "+v"(neg));                   // keeps this a real branch
-#pragma unroll
-                        for (int r = 15; r >= 0; --r) neg = __builtin_amdgcn_alignbit(neg, __float_as_uint(acc[a][b][r]), 31);
-                        m = hit ? (~neg & 0xffffu) : 0u;
-                    }
+                    for (int r = 15; r >= 0; --r) neg = __builtin_amdgcn_alignbit(neg, __float_as_uint(acc[a][b][r]), 31);
+                    const uint32_t m = valid ? (~neg & 0xffffu) : 0u;
                     msk[a * MR + b] = m;
                     mine += __popc(m);
                 }
@@ -469,54 +488,65 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
             if (__builtin_amdgcn_ballot_w64(mine != 0) != 0) {          // uniform within the wavefront
                 const uint32_t incl = wave_inclusive_sum(mine);
                 uint32_t wave_base = 0;
-                if (lane == 63) wave_base = atomicAdd(total_s, incl);
+                if (fresh_lane() == 63) wave_base = atomicAdd(total_s, incl);
                 uint32_t slot = (uint32_t)__builtin_amdgcn_readlane((int)wave_base, 63) + incl - mine;
                 // Pass 2, survivors only, all lanes in parallel: each lane takes the first set bit of its
                 // own mask, fetches that accumulator register with a two-level select (registers cannot
-                // be indexed per lane), and stages the key; the loop repeats while any lane of the
-                // wavefront has bits left (a lane seldom holds two survivors of one block).
+                // be indexed per lane) and stages (value, row id, query); the key is finished when the
+                // list is flushed.  The first round over the blocks is straight-line code, so that the
+                // blocks' instructions interleave; lanes that hold a second survivor of one block (few)
+                // are served by a loop afterwards.
+                auto pick = [&](int a, int b, int r) __attribute__((always_inline)) {
+                    const int lo = r & 3, hi = (r >> 2) & 3;
+                    const uint64_t lo1 = __builtin_amdgcn_ballot_w64(lo == 1), lo3 = __builtin_amdgcn_ballot_w64(lo == 3);
+                    const uint64_t lo23 = __builtin_amdgcn_ballot_w64(lo >= 2);
+                    float g4[4];
 #pragma unroll
-                for (int b = 0; b < MR; ++b) {
-                    int opaque = 0;
-                    asm volatile("" : "+v"(opaque));
-                    const int half = (lane >> 5) + opaque, l32 = (lane & 31) + opaque;
-                    const int32_t id = (int32_t)(t * TILE_ROWS + (wr * MR + b) * 32 + l32);
-                    const float inve = inv_r[b];
-                    const float norm = 1.0f / inve;
-                    const float nh_v = dec16(enc16(norm)), nl_v = dec16(enc16(norm - nh_v));
+                    for (int k = 0; k < 4; ++k)
+                        g4[k] = lane_select(lane_select(acc[a][b][4 * k], acc[a][b][4 * k + 1], lo1),
+                                            lane_select(acc[a][b][4 * k + 2], acc[a][b][4 * k + 3], lo3), lo23);
+                    return lane_select(lane_select(g4[0], g4[1], __builtin_amdgcn_ballot_w64(hi == 1)),
+                                       lane_select(g4[2], g4[3], __builtin_amdgcn_ballot_w64(hi == 3)),
+                                       __builtin_amdgcn_ballot_w64(hi >= 2));
+                };
+                auto stage_one = [&](int a, int b, int r, float av) __attribute__((always_inline)) {   // lanes with a survivor
+                    const int ln = fresh_lane(), half = ln >> 5, l32 = ln & 31;
+                    const int32_t id = (int32_t)(t * TILE_ROWS + (wr_u * MR + b) * 32 + l32);
+                    const int ql = (wq_u * MQ + a) * 32 + 4 * half + 8 * ((r >> 2) & 3) + (r & 3);
+                    if (slot < (uint32_t)SCAN_LIST_CAP) {
+                        lkey[slot] = ((uint64_t)__float_as_uint(av) << 32) | (uint32_t)id;
+                        lq[slot] = (uint32_t)ql;
+                    } else {   // list full (a very loose threshold): fall back to the direct path
+                        uint32_t pos = atomicAdd(cnt + q0 + ql, 1u);
+                        if (pos < (uint32_t)SURV_CAP) surv[(int64_t)(q0 + ql) * SURV_CAP + pos] = finish_key(av, ql, id, invnorm[id]);
+                    }
+                    ++slot;
+                };
+                uint32_t rest = 0;
+#pragma unroll
+                for (int b = 0; b < MR; ++b)
 #pragma unroll
                     for (int a = 0; a < MQ; ++a) {
-                        uint32_t m = msk[a * MR + b];
-                        const int qb = (wq * MQ + a) * 32 + 4 * half;
-                        while (__builtin_amdgcn_ballot_w64(m != 0) != 0) {
-                            const int r = __builtin_ctz(m | 0x10000u);     // 16 for a lane without bits
-                            const int lo = r & 3, hi = (r >> 2) & 3;
-                            const uint64_t lo1 = __builtin_amdgcn_ballot_w64(lo == 1), lo3 = __builtin_amdgcn_ballot_w64(lo == 3);
-                            const uint64_t lo23 = __builtin_amdgcn_ballot_w64(lo >= 2);
-                            float g4[4];
+                        const uint32_t m = msk[a * MR + b];
+                        const int r = __builtin_ctz(m | 0x10000u);          // 16 for a lane without bits
+                        const float av = pick(a, b, r);
+                        if (m) stage_one(a, b, r, av);
+                        msk[a * MR + b] = m & (m - 1);
+                        rest |= m & (m - 1);
+                    }
+                if (__builtin_amdgcn_ballot_w64(rest != 0) != 0) {
 #pragma unroll
-                            for (int k = 0; k < 4; ++k)
-                                g4[k] = lane_select(lane_select(acc[a][b][4 * k], acc[a][b][4 * k + 1], lo1),
-                                                    lane_select(acc[a][b][4 * k + 2], acc[a][b][4 * k + 3], lo3), lo23);
-                            const float av = lane_select(lane_select(g4[0], g4[1], __builtin_amdgcn_ballot_w64(hi == 1)),
-                                                         lane_select(g4[2], g4[3], __builtin_amdgcn_ballot_w64(hi == 3)),
-                                                         __builtin_amdgcn_ballot_w64(hi >= 2));
-                            if (m) {
-                                const int ql = qb + 8 * hi + lo;
-                                const uint32_t tp = thp_s[ql];
-                                const float th = dec16((uint16_t)(tp & 0xffffu)), tl = dec16((uint16_t)(tp >> 16));
-                                const float dot = av + (th * nh_v + th * nl_v + tl * nh_v);
-                                const uint64_t key = pack_key(dot * inve * invq_s[ql], id);
-                                if (slot < (uint32_t)SCAN_LIST_CAP) { lkey[slot] = key; lq[slot] = (uint32_t)ql; }
-                                else {   // list full (a very loose threshold): fall back to the direct path
-                                    uint32_t pos = atomicAdd(cnt + q0 + ql, 1u);
-                                    if (pos < (uint32_t)SURV_CAP) surv[(int64_t)(q0 + ql) * SURV_CAP + pos] = key;
-                                }
-                                ++slot;
+                    for (int b = 0; b < MR; ++b)
+#pragma unroll
+                        for (int a = 0; a < MQ; ++a) {
+                            uint32_t m = msk[a * MR + b];
+                            while (__builtin_amdgcn_ballot_w64(m != 0) != 0) {
+                                const int r = __builtin_ctz(m | 0x10000u);
+                                const float av = pick(a, b, r);
+                                if (m) stage_one(a, b, r, av);
                                 m &= m - 1;
                             }
                         }
-                    }
                 }
             }
             // The list is carried from tile to tile and written out every `flush_every` tiles (the host
@@ -543,8 +573,11 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
     gload(gbA);
     __syncthreads();
     load_invnorm(0);
+    tile_prepare();
     for (int ti = 0; ti < my_tiles; ++ti) {
         tile_init(ti);
+        tile_now = ti;
+        if constexpr (DT == 0) load_invnorm(ti + 1);
         if constexpr (DT != 0) {
 #pragma unroll
             for (int a = 0; a < MQ; ++a) af[a] = frag(0, offA0, a);
@@ -558,6 +591,7 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
         phase(0, gbB, gqB, std::true_type{});
         phase(1, gbA, gqA, std::false_type{});
         epilogue(ti);
+        tile_prepare();
     }
 }
 
