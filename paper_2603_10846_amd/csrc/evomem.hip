@@ -224,22 +224,30 @@ const char* mem_strerror(int s) {
 namespace {
 
 // Scan plan: tile strides of the passes, sparsest first.  The sparsest pass has no threshold, so it
-// may cover at most SURV_CAP rows; each denser pass divides the stride by `ratio`, chosen so that
-// about k1 * ratio rows (a quarter of the survivor slots) are expected to pass its threshold.
+// may cover at most SURV_CAP rows, and it is made as large as that allows (a larger sample gives the
+// next pass a tighter threshold).  Each denser pass divides the stride by `ratio`, chosen so that
+// about k1 * ratio rows (a quarter of the survivor slots) are expected to pass its threshold; the
+// step up to the sparsest pass is whatever factor <= ratio fills its row budget.
 std::vector<Level> plan_levels(int64_t N, int k1) {
     const int nt = (int)((N + TILE_ROWS - 1) / TILE_ROWS);
+    const int cap_tiles = SURV_CAP / TILE_ROWS;
     int ratio = SURV_CAP / (4 * k1);
     if (ratio > 16) ratio = 16;
     if (ratio < 2) ratio = 2;
     std::vector<int> strides{1};
-    while ((nt + strides.back() - 1) / strides.back() > SURV_CAP / TILE_ROWS) strides.push_back(strides.back() * ratio);
+    for (;;) {
+        const int U = (nt + strides.back() - 1) / strides.back();
+        if (U <= cap_tiles) break;
+        const int need = (U + cap_tiles - 1) / cap_tiles;          // >= 2
+        strides.push_back(strides.back() * (need < ratio ? need : ratio));
+    }
     std::vector<Level> lv;
     for (int i = (int)strides.size() - 1; i >= 0; --i) {
         Level L;
         L.stride = strides[i];
         const int U = (nt + L.stride - 1) / L.stride;
         if (i == (int)strides.size() - 1) { L.rho = 0; L.ntiles = U; }
-        else { L.rho = ratio; L.ntiles = U - (U + ratio - 1) / ratio; }
+        else { L.rho = strides[i + 1] / strides[i]; L.ntiles = U - (U + L.rho - 1) / L.rho; }
         if (L.ntiles > 0) lv.push_back(L);
     }
     return lv;

@@ -382,12 +382,26 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
             cnt_s[i] = 0;
         }
         __syncthreads();
-        for (uint32_t e = tid; e < total; e += NT) {
-            uint32_t ql = lq[e] & 0xffffu, rank = lq[e] >> 16;
-            uint32_t pos = base_s[ql] + rank;
-            if (pos < (uint32_t)SURV_CAP) {
-                const int32_t id = (int32_t)(uint32_t)lkey[e];
-                surv[(int64_t)(q0 + ql) * SURV_CAP + pos] = finish_key(__uint_as_float((uint32_t)(lkey[e] >> 32)), (int)ql, id, invnorm[id]);
+        // four entries per lane at a time, so that their inverse-norm reads are in flight together
+        for (uint32_t e0 = tid; e0 < total; e0 += 4 * NT) {
+            float inv[4];
+            uint64_t ent[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const uint32_t e = e0 + k * NT;
+                ent[k] = lkey[e < total ? e : e0];
+                inv[k] = invnorm[(int32_t)(uint32_t)ent[k]];
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const uint32_t e = e0 + k * NT;
+                if (e < total) {
+                    const uint32_t ql = lq[e] & 0xffffu, rank = lq[e] >> 16;
+                    const uint32_t pos = base_s[ql] + rank;
+                    if (pos < (uint32_t)SURV_CAP)
+                        surv[(int64_t)(q0 + ql) * SURV_CAP + pos] =
+                            finish_key(__uint_as_float((uint32_t)(ent[k] >> 32)), (int)ql, (int32_t)(uint32_t)ent[k], inv[k]);
+                }
             }
         }
         __syncthreads();
