@@ -423,10 +423,19 @@ extern "C" int mem_update_q(evomem_t* h, const int32_t* ids_dev, int64_t M, int 
     if (!ids_dev || !rewards_dev) return MEM_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     uint32_t* counters = (uint32_t*)(h->ws + h->w.counters);
+    static bool lds_set[16] = {};          // the kernel's LDS list can exceed the default 64 KB limit
+    if (!lds_set[h->device & 15]) {
+        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void*>(k_update_q), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   (UPD_CHUNK + UPD_PAD) * 8));
+        lds_set[h->device & 15] = true;
+    }
     for (int64_t off = 0; off < M; off += UPD_CHUNK) {
         int m = (int)(M - off < UPD_CHUNK ? M - off : UPD_CHUNK);
-        hipLaunchKernelGGL(k_update_q, dim3(1), dim3(1024), 0, st, ids_dev + off, rewards_dev + off, m,
-                           h->q + (int64_t)stage * h->capacity, h->N, alpha, counters);
+        const int lg = upd_log2_buckets(m);
+        int npad = 2;                      // a bucket may receive every pair of the launch
+        while (npad < m) npad <<= 1;
+        hipLaunchKernelGGL(k_update_q, dim3(1u << lg), dim3(1024), (size_t)(npad + UPD_PAD) * 8, st, ids_dev + off, rewards_dev + off, m,
+                           h->q + (int64_t)stage * h->capacity, h->N, alpha, counters, lg);
         LAUNCHCHK();
     }
     return MEM_OK;
