@@ -39,12 +39,77 @@ def measured_traffic(workload):
     return int(fields["traffic_bytes_per_launch"])
 
 
+def run_stream(torch, binding, synth):
+    """The growing bank: starts at 1M entries and grows to 8M by 64K-entry appends (d = 4096, fp16
+    store); every step appends a chunk, retrieves for B = 128 fresh queries (k1 = 256, k2 = 32,
+    lambda = 0.7, stages alternating) and updates the Q values of the B*k2 returned ids with
+    Bernoulli(0.2) rewards.  Rows and queries are seeded normalised Gaussians generated on the device
+    (68.7 GB of rows: generating them on the host would take longer than the run).  Every call is
+    timed with events on the stream it runs on; one JSON line with samples along the growth."""
+    w = synth.STREAM
+    dev = torch.device("cuda:0")
+    N0, steps, chunk = w.extra["N0"], w.extra["steps"], synth.CHUNK_ROWS
+    bank = binding.MemoryBank(w.d, w.dtype, w.N, max_B=w.B, max_k1=w.k1)
+    g = torch.Generator(device=dev).manual_seed(synth.SEED + 5)
+
+    def rows(n):
+        x = torch.randn((n, w.d), device=dev, generator=g)
+        return x / x.norm(dim=1, keepdim=True)
+    for _ in range(N0 // chunk):
+        bank.append(rows(chunk))
+    out = (torch.empty((w.B, w.k2), dtype=torch.int32, device=dev),
+           torch.empty((w.B, w.k2), dtype=torch.float32, device=dev), None, None)
+    bank.profile_enable(True)
+    rec = []
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    for t in range(steps):
+        new, q = rows(chunk), rows(w.B)
+        rewards = (torch.rand(w.B * w.k2, device=dev, generator=g) < 0.2).float()
+        e = [ev() for _ in range(4)]
+        torch.cuda.synchronize()
+        e[0].record(); bank.append(new)
+        e[1].record(); ids, _, _, _ = bank.retrieve(q, t % 2, w.k1, w.k2, w.lam, out=out)
+        e[2].record(); bank.update_q(ids.view(-1), t % 2, rewards, w.alpha)
+        e[3].record(); torch.cuda.synchronize()
+        prof = bank.profile_read()
+        dense_ms, dense_rows = max(prof, key=lambda p: p[1])
+        rec.append({"step": t, "N": bank.size(), "append_ms": e[0].elapsed_time(e[1]), "retrieve_ms": e[1].elapsed_time(e[2]),
+                    "update_ms": e[2].elapsed_time(e[3]), "dense_ms": dense_ms, "dense_rows": dense_rows})
+        if t % 16 == 0:
+            print(f"# step {t} N={bank.size()} retrieve {rec[-1]['retrieve_ms']:.3f} ms", file=sys.stderr, flush=True)
+    assert bank.counters() == (0, 0)
+    elem = 2
+    samples = []
+    for t in (0, 27, 55, 83, 111):
+        r = rec[t]
+        samples.append({"step": t, "N": r["N"], "retrieve_ms": round(r["retrieve_ms"], 3),
+                        "queries_per_s": round(w.B / (r["retrieve_ms"] * 1e-3), 1),
+                        "store_GBps_whole_retrieve": round(r["N"] * w.d * elem / (r["retrieve_ms"] * 1e-3) / 1e9, 1),
+                        "dense_pass_GBps": round(r["dense_rows"] * w.d * elem / (r["dense_ms"] * 1e-3) / 1e9, 1),
+                        "append_ms": round(r["append_ms"], 3),
+                        "append_GBps": round(chunk * w.d * (4 + elem) / (r["append_ms"] * 1e-3) / 1e9, 1),
+                        "update_ms": round(r["update_ms"], 4)})
+    total_ms = sum(r["append_ms"] + r["retrieve_ms"] + r["update_ms"] for r in rec)
+    last = rec[-1]
+    achieved = last["dense_rows"] * w.d * elem / (last["dense_ms"] * 1e-3) / 1e9
+    print(json.dumps({
+        "metric": "retrieval queries/sec (stream: N 1M -> 8M, d=4096 fp16, B=128)",
+        "value": round(w.B * steps / (total_ms * 1e-3), 1), "unit": "queries/s", "n_gpus": 1, "steps": steps, "warmup": 0,
+        "ms_per_step": round(total_ms / steps, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": "stream: append 65536 + retrieve B=128 k1=256 k2=32 lambda=0.7 + update_q 4096, 112 steps"},
+        "roofline": {"bound": "hbm", "kernel": "k_scan_mfma (densest pass, last step, N=8M)", "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None},
+        "cpu_baseline": None, "samples": samples}))
+    bank.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="clustered", choices=["clustered", "mid", "large", "stream1m"])
+    ap.add_argument("--workload", default="clustered", choices=["clustered", "mid", "large", "stream1m", "stream"])
     ap.add_argument("--batch", type=int, default=0, help="override the workload's query batch size B")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-queries", type=int, default=0, help="oracle sample size (0: 16 per thread, at most B)")
@@ -68,6 +133,8 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_probe_bytes_read": src.numel() * 4, "copy_probe_bytes_written": src.numel() * 4}))
         return
+    if args.workload == "stream":
+        return run_stream(torch, binding, synth)
     w = {"clustered": synth.CLUSTERED, "mid": synth.MID, "large": synth.LARGE,
          "stream1m": synth.scaled(synth.STREAM, N=1048576)}[args.workload]
     if args.batch:
