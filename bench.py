@@ -109,7 +109,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="clustered", choices=["clustered", "mid", "large", "stream1m", "stream"])
+    ap.add_argument("--workload", default="clustered", choices=["clustered", "tiny", "mid", "large", "stream1m", "stream"])
     ap.add_argument("--batch", type=int, default=0, help="override the workload's query batch size B")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-queries", type=int, default=0, help="oracle sample size (0: 16 per thread, at most B)")
@@ -135,7 +135,7 @@ def main():
         return
     if args.workload == "stream":
         return run_stream(torch, binding, synth)
-    w = {"clustered": synth.CLUSTERED, "mid": synth.MID, "large": synth.LARGE,
+    w = {"clustered": synth.CLUSTERED, "tiny": synth.TINY, "mid": synth.MID, "large": synth.LARGE,
          "stream1m": synth.scaled(synth.STREAM, N=1048576)}[args.workload]
     if args.batch:
         w = synth.scaled(w, B=args.batch)

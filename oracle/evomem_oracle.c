@@ -193,6 +193,82 @@ int orc_rerank(const int32_t* cand_ids, const double* cand_sims, int count,
     return 0;
 }
 
+/* ---------- epsilon-greedy selection over the pool (Sec. 3.3, Stage 1: the drafting context is
+ * drawn from the pool C(x) by an epsilon-greedy policy; Sec. 4.4 names the same policy) ----------
+ *
+ * Reading: the k2 slots are filled in order.  For slot j, with probability eps the slot takes a
+ * uniformly random member of the pool that is not chosen yet, otherwise the best member not chosen
+ * yet (score desc, id asc).  eps = 0 is the plain value filter above.
+ * Random numbers: Philox-4x32 with 10 rounds (Salmon, Moraes, Dror, Shaw: "Parallel random numbers:
+ * as easy as 1, 2, 3", SC'11), key = the 64-bit seed, counter = (step low, step high, query, slot).
+ * Word 0 decides exploration: explore iff word0 < floor(eps * 2^32) (compared as 64-bit integers, so
+ * eps = 1 always explores).  Word 1 picks the member: index floor(word1 * remaining / 2^32) into the
+ * not-yet-chosen members in greedy order.  Integer decisions only, so both sides agree exactly.
+ */
+void orc_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        uint64_t p0 = (uint64_t)0xD2511F53u * (uint64_t)c0;     /* multipliers M0, M1 of the 4x32 variant */
+        uint64_t p1 = (uint64_t)0xCD9E8D57u * (uint64_t)c2;
+        uint32_t hi0 = (uint32_t)(p0 >> 32), lo0 = (uint32_t)p0;
+        uint32_t hi1 = (uint32_t)(p1 >> 32), lo1 = (uint32_t)p1;
+        uint32_t n0 = hi1 ^ c1 ^ k0;
+        uint32_t n1 = lo1;
+        uint32_t n2 = hi0 ^ c3 ^ k1;
+        uint32_t n3 = lo0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += 0x9E3779B9u;                                      /* Weyl increments of the key */
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* As orc_rerank, with epsilon-greedy slot filling.  explored (may be NULL) gets 1 for slots filled
+ * by the random branch.  query_index is the query's row in its batch (part of the counter). */
+int orc_rerank_eps(const int32_t* cand_ids, const double* cand_sims, int count,
+                   const float* qtable, double lam, int k2, float eps, uint64_t seed, uint64_t step,
+                   uint32_t query_index, int32_t* out_ids, float* out_scores_f32, double* out_scores_f64,
+                   unsigned char* explored) {
+    if (count < 0 || k2 < 1 || !(eps >= 0.0f && eps <= 1.0f)) return 1;
+    int32_t* ord_ids = (int32_t*)malloc(sizeof(int32_t) * (size_t)(count + 1));
+    double* ord_sc = (double*)malloc(sizeof(double) * (size_t)(count + 1));
+    unsigned char* taken = (unsigned char*)calloc((size_t)(count + 1), 1);
+    /* greedy order of the whole pool */
+    int rc = orc_rerank(cand_ids, cand_sims, count, qtable, lam, count > 0 ? count : 1, ord_ids, NULL, ord_sc);
+    if (rc) { free(ord_ids); free(ord_sc); free(taken); return rc; }
+    const uint64_t thr = (uint64_t)((double)eps * 4294967296.0);
+    const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    for (int j = 0; j < k2; ++j) {
+        int remaining = count - j;
+        if (remaining <= 0) {
+            out_ids[j] = -1;
+            if (out_scores_f32) out_scores_f32[j] = -INFINITY;
+            if (out_scores_f64) out_scores_f64[j] = -INFINITY;
+            if (explored) explored[j] = 0;
+            continue;
+        }
+        const uint32_t ctr[4] = {(uint32_t)step, (uint32_t)(step >> 32), query_index, (uint32_t)j};
+        uint32_t rnd[4];
+        orc_philox4x32_10(ctr, key, rnd);
+        int explore = (uint64_t)rnd[0] < thr;
+        int want = explore ? (int)(((uint64_t)rnd[1] * (uint64_t)remaining) >> 32) : 0;   /* index among the free ones */
+        int pos = -1;
+        for (int i = 0, seen = 0; i < count; ++i) {
+            if (taken[i]) continue;
+            if (seen == want) { pos = i; break; }
+            ++seen;
+        }
+        taken[pos] = 1;
+        out_ids[j] = ord_ids[pos];
+        if (out_scores_f32) out_scores_f32[j] = (float)ord_sc[pos];
+        if (out_scores_f64) out_scores_f64[j] = ord_sc[pos];
+        if (explored) explored[j] = (unsigned char)explore;
+    }
+    free(ord_ids); free(ord_sc); free(taken);
+    return 0;
+}
+
 /* ---------- step 3: unified value update ---------- */
 
 /* Reference: fp64 state seeded from the fp32 table, rounded back to fp32 once at the end.

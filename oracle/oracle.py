@@ -44,6 +44,12 @@ def _load():
         L.orc_sims_of.restype = C.c_int
         L.orc_rerank.argtypes = [i32p, f64p, C.c_int, f32p, C.c_double, C.c_int, i32p, f32p, f64p]
         L.orc_rerank.restype = C.c_int
+        u32p, u8p = C.POINTER(C.c_uint32), C.POINTER(C.c_ubyte)
+        L.orc_philox4x32_10.argtypes = [u32p, u32p, u32p]
+        L.orc_philox4x32_10.restype = None
+        L.orc_rerank_eps.argtypes = [i32p, f64p, C.c_int, f32p, C.c_double, C.c_int, C.c_float, C.c_uint64, C.c_uint64,
+                                     C.c_uint32, i32p, f32p, f64p, u8p]
+        L.orc_rerank_eps.restype = C.c_int
         L.orc_update_q64.argtypes = [f32p, C.c_int64, i32p, f32p, C.c_int64, C.c_double]
         L.orc_update_q64.restype = C.c_int64
         L.orc_update_q32.argtypes = [f32p, C.c_int64, i32p, f32p, C.c_int64, C.c_float]
@@ -132,6 +138,34 @@ def rerank(cand_ids, cand_sims, qtable, lam: float, k2: int):
     if rc:
         raise RuntimeError("orc_rerank failed")
     return ids, s32, s64
+
+
+def philox4x32_10(ctr, key):
+    """Philox-4x32-10 block: ctr 4 and key 2 uint32 words -> 4 uint32 words."""
+    ctr = np.ascontiguousarray(ctr, np.uint32)
+    key = np.ascontiguousarray(key, np.uint32)
+    out = np.empty(4, np.uint32)
+    _load().orc_philox4x32_10(_p(ctr, C.c_uint32), _p(key, C.c_uint32), _p(out, C.c_uint32))
+    return out
+
+
+def rerank_eps(cand_ids, cand_sims, qtable, lam: float, k2: int, eps: float, seed: int, step: int, query_index: int):
+    """Epsilon-greedy slot filling for ONE query (Sec. 3.3): returns (ids, scores f32, scores f64, explored u8)."""
+    cand_ids = np.ascontiguousarray(cand_ids, np.int32)
+    cand_sims = np.ascontiguousarray(cand_sims, np.float64)
+    keep = cand_ids >= 0
+    cand_ids, cand_sims = np.ascontiguousarray(cand_ids[keep]), np.ascontiguousarray(cand_sims[keep])
+    qtable = _f32(qtable)
+    ids = np.empty(k2, np.int32)
+    s32 = np.empty(k2, np.float32)
+    s64 = np.empty(k2, np.float64)
+    ex = np.empty(k2, np.uint8)
+    rc = _load().orc_rerank_eps(_p(cand_ids, C.c_int32), _p(cand_sims, C.c_double), cand_ids.size,
+                                _p(qtable, C.c_float), lam, k2, float(np.float32(eps)), seed, step, query_index,
+                                _p(ids, C.c_int32), _p(s32, C.c_float), _p(s64, C.c_double), _p(ex, C.c_ubyte))
+    if rc:
+        raise RuntimeError("orc_rerank_eps failed")
+    return ids, s32, s64, ex
 
 
 def update_q64(qtable, ids, rewards, alpha: float):

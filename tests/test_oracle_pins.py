@@ -340,3 +340,117 @@ def test_retrieve_end_to_end_matches_python_definition(orc):
         sims = [-p[0] for p in brute[b]]
         bi, bs = _brute_rerank(ids, sims, qt, 0.5, 4)
         assert out["ids"][b].tolist() == bi and np.allclose(out["scores64"][b], bs, atol=1e-9, rtol=0)
+
+
+# ----------------------------------------------------------------------------- epsilon-greedy selection (Sec. 3.3)
+
+def _philox_py(ctr, key):
+    """Philox-4x32-10 written out with Python integers from the generator's definition (independent of the C code)."""
+    c = list(ctr)
+    k = list(key)
+    for _ in range(10):
+        p0 = 0xD2511F53 * c[0]
+        p1 = 0xCD9E8D57 * c[2]
+        c = [((p1 >> 32) ^ c[1] ^ k[0]) & 0xffffffff, p1 & 0xffffffff, ((p0 >> 32) ^ c[3] ^ k[1]) & 0xffffffff, p0 & 0xffffffff]
+        k = [(k[0] + 0x9E3779B9) & 0xffffffff, (k[1] + 0xBB67AE85) & 0xffffffff]
+    return c
+
+
+def test_philox_known_answers(orc):
+    kat = json.load(open(os.path.join(GOLD, "philox_kat.json")))
+    for v in kat["vectors"]:
+        ctr, key = [int(x, 16) for x in v["ctr"]], [int(x, 16) for x in v["key"]]
+        want = [int(x, 16) for x in v["out"]]
+        assert list(orc.philox4x32_10(ctr, key)) == want
+        assert _philox_py(ctr, key) == want
+    rng = np.random.default_rng(3)
+    for _ in range(200):
+        ctr, key = [int(x) for x in rng.integers(0, 2**32, 4)], [int(x) for x in rng.integers(0, 2**32, 2)]
+        assert list(orc.philox4x32_10(ctr, key)) == _philox_py(ctr, key)
+
+
+def _pool(rng, n_table=500, count=40):
+    ids = rng.permutation(n_table)[:count].astype(np.int32)
+    sims = np.sort(rng.uniform(0.2, 0.9, count))[::-1].copy()
+    q = rng.uniform(-1, 1, n_table).astype(np.float32)
+    return ids, sims, q
+
+
+def test_eps_zero_is_the_value_filter(orc):
+    rng = np.random.default_rng(4)
+    for _ in range(20):
+        ids, sims, q = _pool(rng)
+        lam = float(rng.uniform(0, 1))
+        g_ids, g_s32, g_s64 = orc.rerank(ids, sims, q, lam, 8)
+        e_ids, e_s32, e_s64, ex = orc.rerank_eps(ids, sims, q, lam, 8, 0.0, 99, 7, 3)
+        assert np.array_equal(g_ids, e_ids) and np.array_equal(g_s64, e_s64) and not ex.any()
+
+
+def test_eps_greedy_against_brute_force(orc):
+    """Slot by slot in Python: greedy order from orc.rerank over the whole pool, draws from the Python Philox."""
+    rng = np.random.default_rng(5)
+    for trial in range(30):
+        count = int(rng.integers(1, 30))
+        ids, sims, q = _pool(rng, count=count)
+        lam, k2 = float(rng.uniform(0, 1)), int(rng.integers(1, 12))
+        eps = np.float32(rng.choice([0.05, 0.3, 0.5, 1.0]))
+        seed, step, qi = int(rng.integers(0, 2**63)), int(rng.integers(0, 2**40)), int(rng.integers(0, 1000))
+        order, _, order_sc = orc.rerank(ids, sims, q, lam, count)
+        free = list(range(count))
+        want_ids, want_sc, want_ex = [], [], []
+        thr = int(float(eps) * 4294967296.0)
+        for j in range(k2):
+            if not free:
+                want_ids.append(-1); want_sc.append(-np.inf); want_ex.append(0)
+                continue
+            r = _philox_py([step & 0xffffffff, step >> 32, qi, j], [seed & 0xffffffff, seed >> 32])
+            explore = r[0] < thr
+            pick = (r[1] * len(free)) >> 32 if explore else 0
+            pos = free.pop(pick)
+            want_ids.append(int(order[pos])); want_sc.append(float(order_sc[pos])); want_ex.append(int(explore))
+        got_ids, _, got_sc, got_ex = orc.rerank_eps(ids, sims, q, lam, k2, float(eps), seed, step, qi)
+        assert list(got_ids) == want_ids and list(got_ex) == want_ex
+        assert np.array_equal(got_sc, np.array(want_sc))
+        chosen = [i for i in want_ids if i >= 0]
+        assert len(set(chosen)) == len(chosen) and set(chosen) <= set(ids.tolist())
+
+
+def test_eps_one_explores_every_slot_and_rate_matches_eps(orc):
+    rng = np.random.default_rng(6)
+    ids, sims, q = _pool(rng, count=64)
+    first = np.zeros(64, int)
+    order, _, _ = orc.rerank(ids, sims, q, 0.5, 64)
+    rank_of = {int(i): r for r, i in enumerate(order)}
+    n_explored = 0
+    trials = 3000
+    for t in range(trials):
+        e_ids, _, _, ex = orc.rerank_eps(ids, sims, q, 0.5, 4, 1.0, 1234, t, 0)
+        assert ex.all()
+        first[rank_of[int(e_ids[0])]] += 1
+        _, _, _, ex2 = orc.rerank_eps(ids, sims, q, 0.5, 4, 0.25, 1234, t, 1)
+        n_explored += int(ex2.sum())
+    # first slot under eps = 1: uniform over the 64 members (expected 46.9 each; 6 sigma bounds)
+    assert first.min() > 46.9 - 6 * 6.8 and first.max() < 46.9 + 6 * 6.8
+    # exploration rate: 12000 Bernoulli(0.25) draws, 5 sigma
+    assert abs(n_explored / (4 * trials) - 0.25) < 5 * math.sqrt(0.25 * 0.75 / (4 * trials))
+
+
+def test_eps_planted_mistakes_are_caught(orc):
+    """The brute-force pin above must tell apart the plausible wrong readings: picking among ALL members instead
+    of the free ones, or using word 0 for the index."""
+    rng = np.random.default_rng(7)
+    ids, sims, q = _pool(rng, count=12)
+    order, _, _ = orc.rerank(ids, sims, q, 0.5, 12)
+    differs_all, differs_word = False, False
+    for step in range(200):
+        got, _, _, ex = orc.rerank_eps(ids, sims, q, 0.5, 6, 1.0, 5, step, 0)
+        free = list(range(12))
+        wrong_all, wrong_word = [], []
+        free2 = list(range(12))
+        for j in range(6):
+            r = _philox_py([step, 0, 0, j], [5, 0])
+            wrong_all.append(int(order[(r[1] * 12) >> 32]))
+            wrong_word.append(int(order[free2.pop((r[0] * len(free2)) >> 32)]))
+        differs_all |= wrong_all != list(got)
+        differs_word |= wrong_word != list(got)
+    assert differs_all and differs_word
