@@ -106,6 +106,28 @@ int mem_retrieve(evomem_t* h, const float* queries_dev, int B, int stage, int k1
                  int32_t* out_cand_ids_dev, float* out_cand_sims_dev, void* hip_stream);
 
 /*
+ * Retrieve with epsilon-greedy selection of the final items (Sec. 3.3, Stage 1: the drafting
+ * context is drawn from the pool C(x) by an epsilon-greedy policy over Q_1; Sec. 4.4 uses the same
+ * policy for both stages).  The pool and the scores are those of mem_retrieve; the k2 slots are
+ * filled in order: with probability eps a slot takes a uniformly random member of the pool that is
+ * not chosen yet, otherwise the best one not chosen yet (score desc, id asc).  eps = 0 gives
+ * exactly mem_retrieve's result.
+ * The draws are a pure function of (seed, step, query row, slot): Philox-4x32 with 10 rounds, key =
+ * seed (low word, high word), counter = (step low, step high, query row, slot).  Output word 0
+ * decides: explore iff word0 < floor(eps * 2^32), compared as 64-bit integers.  Output word 1 picks:
+ * index floor(word1 * remaining / 2^32) among the members not chosen yet, in greedy order.  A caller
+ * that passes its iteration counter as `step` can therefore replay any call.
+ *   out_scores_dev    the chosen items' scores (not sorted: slot order)
+ *   out_explored_dev  uint8[B][k2], 1 where the slot was filled by the random branch; may be NULL
+ * Errors: as mem_retrieve, and MEM_EINVAL for eps outside [0,1] or NaN.
+ */
+int mem_retrieve_eps(evomem_t* h, const float* queries_dev, int B, int stage, int k1, int k2,
+                     float lambda, float eps, uint64_t seed, uint64_t step,
+                     int32_t* out_ids_dev, float* out_scores_dev,
+                     int32_t* out_cand_ids_dev, float* out_cand_sims_dev,
+                     unsigned char* out_explored_dev, void* hip_stream);
+
+/*
  * Value update (Sec. 3.2, Eq. "unified update"): for j = 0..M-1 in array order,
  * Q_stage[ids[j]] <- Q + alpha (rewards[j] - Q), each operation rounded to fp32 (no fused
  * multiply-add).  An id that occurs several times receives its rewards one after another in array

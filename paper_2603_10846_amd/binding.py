@@ -32,6 +32,9 @@ SYMBOLS = {
                              C.POINTER(C.c_int64), C.c_void_p]),
     "mem_retrieve": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_float,
                                C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "mem_retrieve_eps": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_float, C.c_float,
+                                   C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                   C.c_void_p]),
     "mem_update_q": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_void_p, C.c_float, C.c_void_p]),
     "mem_size": (C.c_int, [C.c_void_p, C.POINTER(C.c_int64)]),
     "mem_read_q": (C.c_int, [C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p]),
@@ -150,6 +153,21 @@ class MemoryBank:
         _check(self.lib.mem_retrieve(self.h, _ptr(queries), B, stage, k1, k2, lam, _ptr(ids), _ptr(scores),
                                      _ptr(cid), _ptr(csim), _stream()), "mem_retrieve")
         return ids, scores, cid, csim
+
+    def retrieve_eps(self, queries: torch.Tensor, stage: int, k1: int, k2: int, lam: float, eps: float, seed: int,
+                     step: int, want_candidates: bool = False):
+        """Epsilon-greedy selection; returns (ids, scores, cand_ids, cand_sims, explored uint8 [B][k2])."""
+        assert queries.is_cuda and queries.dtype == torch.float32 and queries.is_contiguous()
+        B = queries.shape[0]
+        ids = torch.empty((B, k2), dtype=torch.int32, device=self.device)
+        scores = torch.empty((B, k2), dtype=torch.float32, device=self.device)
+        explored = torch.empty((B, k2), dtype=torch.uint8, device=self.device)
+        cid = torch.empty((B, k1), dtype=torch.int32, device=self.device) if want_candidates else None
+        csim = torch.empty((B, k1), dtype=torch.float32, device=self.device) if want_candidates else None
+        _check(self.lib.mem_retrieve_eps(self.h, _ptr(queries), B, stage, k1, k2, lam, eps, seed, step, _ptr(ids),
+                                         _ptr(scores), _ptr(cid), _ptr(csim), _ptr(explored), _stream()),
+               "mem_retrieve_eps")
+        return ids, scores, cid, csim, explored
 
     def update_q(self, ids: torch.Tensor, stage: int, rewards: torch.Tensor, alpha: float):
         assert ids.is_cuda and ids.dtype == torch.int32 and rewards.dtype == torch.float32

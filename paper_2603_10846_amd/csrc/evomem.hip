@@ -328,9 +328,9 @@ extern "C" int mem_plan_levels(int64_t N, int k1, int* stride, int* rho, int* nt
     return (int)lv.size();
 }
 
-extern "C" int mem_retrieve(evomem_t* h, const float* queries_dev, int B, int stage, int k1, int k2, float lambda,
-                            int32_t* out_ids_dev, float* out_scores_dev, int32_t* out_cand_ids_dev,
-                            float* out_cand_sims_dev, void* hip_stream) {
+static int retrieve_impl(evomem_t* h, const float* queries_dev, int B, int stage, int k1, int k2, float lambda,
+                         int32_t* out_ids_dev, float* out_scores_dev, int32_t* out_cand_ids_dev,
+                         float* out_cand_sims_dev, void* hip_stream, const EpsGreedy& eg) {
     if (!h || B < 0 || B > h->max_B || (stage != 0 && stage != 1) || k1 < 1 || k2 < 1 || k2 > k1 || k1 > h->max_k1)
         return MEM_EINVAL;
     if (!(lambda >= 0.f && lambda <= 1.f)) return MEM_EINVAL;
@@ -411,9 +411,27 @@ extern "C" int mem_retrieve(evomem_t* h, const float* queries_dev, int B, int st
     }
     hipLaunchKernelGGL(k_rerank, dim3(B), dim3(RERANK_T), 0, st, (const uint64_t*)surv, (const uint32_t*)cnt, (const double*)exact,
                        (const float*)(h->q + (int64_t)stage * h->capacity), k1, k2, (double)lambda, out_ids_dev, out_scores_dev,
-                       out_cand_ids_dev, out_cand_sims_dev);
+                       out_cand_ids_dev, out_cand_sims_dev, eg);
     LAUNCHCHK();
     return MEM_OK;
+}
+
+extern "C" int mem_retrieve(evomem_t* h, const float* queries_dev, int B, int stage, int k1, int k2, float lambda,
+                            int32_t* out_ids_dev, float* out_scores_dev, int32_t* out_cand_ids_dev,
+                            float* out_cand_sims_dev, void* hip_stream) {
+    const EpsGreedy greedy{0, 0, 0, nullptr};
+    return retrieve_impl(h, queries_dev, B, stage, k1, k2, lambda, out_ids_dev, out_scores_dev, out_cand_ids_dev,
+                         out_cand_sims_dev, hip_stream, greedy);
+}
+
+extern "C" int mem_retrieve_eps(evomem_t* h, const float* queries_dev, int B, int stage, int k1, int k2, float lambda,
+                                float eps, uint64_t seed, uint64_t step, int32_t* out_ids_dev, float* out_scores_dev,
+                                int32_t* out_cand_ids_dev, float* out_cand_sims_dev, unsigned char* out_explored_dev,
+                                void* hip_stream) {
+    if (!(eps >= 0.f && eps <= 1.f)) return MEM_EINVAL;
+    const EpsGreedy eg{(uint64_t)((double)eps * 4294967296.0), seed, step, out_explored_dev};
+    return retrieve_impl(h, queries_dev, B, stage, k1, k2, lambda, out_ids_dev, out_scores_dev, out_cand_ids_dev,
+                         out_cand_sims_dev, hip_stream, eg);
 }
 
 extern "C" int mem_update_q(evomem_t* h, const int32_t* ids_dev, int64_t M, int stage, const float* rewards_dev,

@@ -180,6 +180,34 @@ __global__ __launch_bounds__(1024) void k_rescore(const void* __restrict__ store
 
 constexpr int RERANK_T = 256;
 
+// One block of the Philox-4x32 counter-based generator with 10 rounds (Salmon et al., SC'11): each
+// round multiplies counter words 0 and 2 by fixed odd constants, crosses the high and low halves
+// with the other two words and the key, and the key advances by fixed Weyl increments.
+struct philox_out { uint32_t w0, w1, w2, w3; };
+__device__ __forceinline__ philox_out philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                                    uint32_t k0, uint32_t k1) {
+    constexpr uint32_t MUL_A = 0xD2511F53u, MUL_B = 0xCD9E8D57u, WEYL_A = 0x9E3779B9u, WEYL_B = 0xBB67AE85u;
+#pragma unroll
+    for (int round = 0; round < 10; ++round) {
+        const uint32_t a_hi = __umulhi(MUL_A, c0), a_lo = MUL_A * c0;
+        const uint32_t b_hi = __umulhi(MUL_B, c2), b_lo = MUL_B * c2;
+        c0 = b_hi ^ c1 ^ k0;
+        c2 = a_hi ^ c3 ^ k1;
+        c1 = b_lo;
+        c3 = a_lo;
+        k0 += WEYL_A;
+        k1 += WEYL_B;
+    }
+    return {c0, c1, c2, c3};
+}
+
+// Parameters of the epsilon-greedy slot filling (Sec. 3.3); threshold 0 and no flag output = greedy.
+struct EpsGreedy {
+    uint64_t threshold;      // floor(eps * 2^32): a slot explores iff its first random word is below it
+    uint64_t seed, step;
+    unsigned char* explored; // [B][k2] or null
+};
+
 // Deterministic sum of one value per thread over a 256-thread workgroup: wavefront butterflies, then
 // the four partial sums added in a fixed order.
 __device__ __forceinline__ double block_sum(double* red, int tid, double x) {
@@ -206,7 +234,7 @@ __global__ __launch_bounds__(RERANK_T) void k_rerank(const uint64_t* __restrict_
                                                 const double* __restrict__ exact, const float* __restrict__ qstage,
                                                 int k1, int k2, double lambda, int32_t* __restrict__ out_ids,
                                                 float* __restrict__ out_scores, int32_t* __restrict__ cand_ids,
-                                                float* __restrict__ cand_sims) {
+                                                float* __restrict__ cand_sims, EpsGreedy eg) {
     __shared__ double v0[KEEP_MAX], v1[MEM_MAX_K1_INTERNAL];
     __shared__ int32_t i0[KEEP_MAX], i1[MEM_MAX_K1_INTERNAL];
     __shared__ double red[4];
@@ -253,13 +281,63 @@ __global__ __launch_bounds__(RERANK_T) void k_rerank(const uint64_t* __restrict_
     if (mine) { v0[tid] = score; i0[tid] = id; }
     __syncthreads();
     const int k2e = k1e < k2 ? k1e : k2;
+    const bool greedy = eg.threshold == 0 && eg.explored == nullptr;
+    int rank = 0;
     if (mine) {
-        int rank = 0;
 #pragma unroll 8
         for (int j = 0; j < k1e; ++j) rank += ranks_before(v0[j], i0[j], score, id);
-        if (rank < k2e) { out_ids[(int64_t)b * k2 + rank] = id; out_scores[(int64_t)b * k2 + rank] = (float)score; }
+        if (greedy && rank < k2e) { out_ids[(int64_t)b * k2 + rank] = id; out_scores[(int64_t)b * k2 + rank] = (float)score; }
     }
-    for (int i = k2e + tid; i < k2; i += RERANK_T) { out_ids[(int64_t)b * k2 + i] = -1; out_scores[(int64_t)b * k2 + i] = -INFINITY; }
+    for (int i = k2e + tid; i < k2; i += RERANK_T) {
+        out_ids[(int64_t)b * k2 + i] = -1;
+        out_scores[(int64_t)b * k2 + i] = -INFINITY;
+        if (eg.explored) eg.explored[(int64_t)b * k2 + i] = 0;
+    }
+    if (greedy) return;                                               // uniform
+
+    // Epsilon-greedy slot filling (Sec. 3.3).  The whole pool is laid out in greedy order; every
+    // slot's draw is computed by its own lane (the draws depend on the slot number only); then one
+    // lane fills the slots in order, because which members are still free depends on the slots before.
+    __shared__ uint32_t word0[MEM_MAX_K1_INTERNAL], word1[MEM_MAX_K1_INTERNAL];
+    if (mine) { v1[rank] = score; i1[rank] = id; }
+    if (tid < k2e) {
+        const philox_out r = philox4x32_10((uint32_t)eg.step, (uint32_t)(eg.step >> 32), (uint32_t)b, (uint32_t)tid,
+                                           (uint32_t)eg.seed, (uint32_t)(eg.seed >> 32));
+        word0[tid] = r.w0;
+        word1[tid] = r.w1;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        uint64_t taken[MEM_MAX_K1_INTERNAL / 64];                     // bit set = chosen (or past the pool's end)
+#pragma unroll
+        for (int w = 0; w < MEM_MAX_K1_INTERNAL / 64; ++w) {
+            const int lo = w * 64;
+            taken[w] = k1e >= lo + 64 ? 0ull : k1e <= lo ? ~0ull : (~0ull << (k1e - lo));
+        }
+        for (int j = 0; j < k2e; ++j) {
+            const bool explore = (uint64_t)word0[j] < eg.threshold;
+            const uint32_t remaining = (uint32_t)(k1e - j);
+            int want = explore ? (int)(((uint64_t)word1[j] * remaining) >> 32) : 0;   // index among the free members
+            int pos = 0;
+#pragma unroll
+            for (int w = 0; w < MEM_MAX_K1_INTERNAL / 64; ++w) {
+                uint64_t fr = ~taken[w];
+                const int c = __popcll(fr);
+                if (want >= 0 && want < c) {
+                    for (int t = 0; t < want; ++t) fr &= fr - 1;              // drop the `want` lowest free bits
+                    const int bit = __ffsll((long long)fr) - 1;
+                    taken[w] |= 1ull << bit;
+                    pos = w * 64 + bit;
+                    want = -1;
+                } else if (want >= 0) {
+                    want -= c;
+                }
+            }
+            out_ids[(int64_t)b * k2 + j] = i1[pos];
+            out_scores[(int64_t)b * k2 + j] = (float)v1[pos];
+            if (eg.explored) eg.explored[(int64_t)b * k2 + j] = explore ? 1 : 0;
+        }
+    }
 }
 
 }  // namespace evk

@@ -324,3 +324,51 @@ def test_stream_workload_reduced(orc):
         assert np.array_equal(bank.read_q(stage).cpu().numpy().view(np.uint32), tables[stage][:n].view(np.uint32))
     assert bank.counters() == (0, 0)
     bank.close()
+
+
+# ----------------------------------------------------------------------------- epsilon-greedy selection (Sec. 3.3)
+
+@pytest.mark.parametrize("dtype,N,d,nq,k1,k2,eps", [
+    ("f32", 3000, 96, 3, 40, 8, 0.3),        # VALU scan
+    ("bf16", 20000, 256, 70, 128, 16, 0.25),  # MFMA scan, pool of the bench configuration
+    ("f16", 9000, 192, 33, 256, 32, 1.0),     # largest pool, every slot random
+    ("f32", 50, 64, 5, 64, 64, 0.5),          # pool smaller than k1, k2 = k1: all members chosen, padding
+])
+def test_retrieve_eps_matches_oracle(orc, dtype, N, d, nq, k1, k2, eps):
+    """Same pool as the greedy call; the slots must be the ones the oracle fills from the GPU's pool with the same
+    (seed, step, query, slot) draws: ids, flags and slot order bit-exact, scores within tolerance."""
+    rng = np.random.default_rng(N + k1)
+    rows, q = _unit(rng, N, d), _unit(rng, nq, d)
+    qtab = rng.uniform(-1, 1, (2, N)).astype(np.float32)
+    bank = _make_bank(dtype, rows, qtab, max_B=128)
+    seed, step, lam, stage = 0x9E3779B97F4A7C15, (1 << 33) + 5, 0.5, 1
+    greedy = parity.gpu_retrieve(bank, torch, q, stage, k1, k2, lam)
+    ids, sc, cid, csim, ex = bank.retrieve_eps(_dev(q), stage, k1, k2, lam, eps, seed, step, want_candidates=True)
+    torch.cuda.synchronize()
+    ids, sc, cid, ex = ids.cpu().numpy(), sc.cpu().numpy(), cid.cpu().numpy(), ex.cpu().numpy()
+    assert np.array_equal(cid, greedy["cand_ids"])                       # the pool does not depend on eps
+    store, qs = orc.round_to_store(rows, DT[dtype]), orc.round_to_store(q, DT[dtype])
+    k1e = min(k1, N)
+    n_explored = 0
+    for b in range(nq):
+        pool = cid[b][:k1e]
+        sims = orc.sims_of(store, qs[b], pool)
+        w_ids, _, w_sc, w_ex = orc.rerank_eps(pool, sims, qtab[stage], lam, k2, eps, seed, step, b)
+        assert np.array_equal(ids[b], w_ids), f"query {b}: {ids[b]} vs {w_ids}"
+        assert np.array_equal(ex[b], w_ex)
+        live = w_ids >= 0
+        assert np.all(np.abs(sc[b][live].astype(np.float64) - w_sc[live]) <= parity.TOL * np.maximum(1.0, np.abs(w_sc[live])))
+        assert np.all(np.isneginf(sc[b][~live]))
+        n_explored += int(w_ex.sum())
+    if eps == 1.0:
+        assert n_explored == nq * min(k2, k1e)
+    # eps = 0 through the same entry point is the greedy result, and a different step gives other draws
+    ids0, sc0, _, _, ex0 = bank.retrieve_eps(_dev(q), stage, k1, k2, lam, 0.0, seed, step)
+    assert np.array_equal(ids0.cpu().numpy(), greedy["ids"]) and not ex0.cpu().numpy().any()
+    assert np.array_equal(sc0.cpu().numpy(), greedy["scores"])
+    if eps >= 0.25 and nq * k2 >= 64:
+        ids2, _, _, _, _ = bank.retrieve_eps(_dev(q), stage, k1, k2, lam, eps, seed, step + 1)
+        assert not np.array_equal(ids2.cpu().numpy(), ids)
+    with pytest.raises(B.MemError):
+        bank.retrieve_eps(_dev(q), stage, k1, k2, lam, 1.5, seed, step)
+    bank.close()
