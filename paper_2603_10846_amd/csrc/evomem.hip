@@ -292,7 +292,7 @@ int launch_mfma_dt(evomem* h, hipStream_t st, int Bp, int qt, const Level& L, in
     switch (qt) {
         case 32: return launch_mfma<DT, 1, 1, 2, 4>(h, st, Bp, L, k1);
         case 64: return launch_mfma<DT, 2, 1, 2, 4>(h, st, Bp, L, k1);
-        case 128: return launch_mfma<DT, 2, 2, 4, 2>(h, st, Bp, L, k1);
+        case 128: return launch_mfma<DT, 2, 2, 2, 4>(h, st, Bp, L, k1);     // 8 wavefronts, 64 x 64 each
         default: return launch_mfma<DT, 4, 2, 2, 4>(h, st, Bp, L, k1);   // 8 wavefronts, 128 x 64 each
     }
 }
