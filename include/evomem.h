@@ -154,7 +154,8 @@ int mem_counters(evomem_t* h, int64_t* skipped_ids, int64_t* overflows);
 
 /* Per-kernel timing with HIP events on the call's stream (off by default).  While on, every
  * launch of the similarity-scan kernel is bracketed by two events (at most 4096 launches are kept
- * between reads).  mem_profile_read synchronises the device and writes, for up to `capacity`
+ * between reads; switching off and on again keeps what was recorded, so a caller can time a
+ * sample of its calls -- each event costs a few microseconds of idle time around the launch).  mem_profile_read synchronises the device and writes, for up to `capacity`
  * launches recorded since the last read, in launch order: ms_out[i] the duration in milliseconds,
  * rows_out[i] the number of bank rows that launch scanned; *n_out is how many were written. */
 int mem_profile_enable(evomem_t* h, int on);

@@ -189,8 +189,7 @@ int mem_profile_enable(evomem_t* h, int on) {
         for (auto& e : h->ev)
             if (hipEventCreate(&e) != hipSuccess) return MEM_EHIP;
     }
-    h->prof_on = on != 0;
-    h->prof_n = 0;
+    h->prof_on = on != 0;      // the records kept so far stay until they are read
     return MEM_OK;
 }
 
