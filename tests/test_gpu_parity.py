@@ -133,6 +133,39 @@ def test_edge_cases(orc):
     bank.close()
 
 
+def test_survivor_list_overflow_is_counted(orc):
+    """More rows tie with the pool's last member than a survivor list holds (8192): the query is counted by
+    mem_counters, the call still returns a valid pool of exact ties, and later calls are unaffected."""
+    rng = np.random.default_rng(107)
+    v = _unit(rng, 1, 128)
+    rows = np.concatenate([np.repeat(v, 16000, axis=0), _unit(rng, 4000, 128)])
+    rows = rows[rng.permutation(len(rows))]
+    copies = set(np.flatnonzero(np.all(rows == v[0], axis=1)).tolist())
+    bank = _make_bank("bf16", rows, max_B=8, max_k1=64)
+    q = np.concatenate([v, _unit(rng, 5, 128)])
+    out = parity.gpu_retrieve(bank, torch, q, 0, 64, 8, 0.0)
+    skipped, overflows = bank.counters()
+    assert skipped == 0 and overflows >= 1
+    pool = out["cand_ids"][0]
+    assert len(set(pool.tolist())) == 64 and set(pool.tolist()) <= copies
+    assert np.all(np.abs(out["cand_sims"][0] - 1.0) < 1e-5)
+    # the queries of the same call whose pools have no such mass of ties match the oracle
+    st, qr = orc.round_to_store(rows, DT["bf16"]), orc.round_to_store(q, DT["bf16"])
+    sims = (qr.astype(np.float64) @ st.astype(np.float64).T)
+    sims /= np.linalg.norm(qr.astype(np.float64), axis=1)[:, None] * np.linalg.norm(st.astype(np.float64), axis=1)[None, :]
+    kth = np.sort(sims, axis=1)[:, -64]
+    crowded = [(sims[b] >= kth[b] - 1e-3).sum() > 4096 for b in range(len(q))]
+    assert crowded[0] and overflows >= 1
+    safe = [b for b in range(len(q)) if not crowded[b]]
+    assert len(safe) >= 3
+    parity.check_retrieve(orc, st, qr, np.zeros(len(rows), np.float32), 64, 8, 0.0, out, sample=safe)
+    before = bank.counters()[1]
+    out2 = parity.gpu_retrieve(bank, torch, q[safe], 0, 64, 8, 0.0)
+    parity.check_retrieve(orc, st, qr[safe], np.zeros(len(rows), np.float32), 64, 8, 0.0, out2)
+    assert bank.counters()[1] == before
+    bank.close()
+
+
 # ----------------------------------------------------------------------------- value update
 
 def _check_update(orc, bank, stage, table, ids, rewards, alpha):
