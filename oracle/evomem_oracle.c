@@ -305,6 +305,44 @@ int64_t orc_update_q32(float* qtable, int64_t N, const int32_t* ids, const float
     return skipped;
 }
 
+/* ---------- rewards of the two stages and their online normalisation ----------
+ *
+ * Stage 1 (Sec. 3.3): +1 for a feasible candidate, -1 otherwise.
+ * Stage 2 (Sec. 3.4): -1 if infeasible, else tanh(log b - log l) with b the best latency so far and l
+ * the measured latency (App. A writes it tanh(log rho) with rho = b / l the speed-up ratio).
+ * Normalisation (Sec. 3.4 "PopArt-style", App. A "Stability of Online Normalization"): sample t is
+ * mapped to (r_t - mu_{t-1}) / max(sigma_{t-1}, sigma_min), clipped to [-clip, clip] if clip > 0,
+ * where mu and sigma are the running mean and POPULATION deviation (1/t form) of all raw rewards
+ * seen before it.  Reading: the statistics cover every raw reward of the stage, the -1 of infeasible
+ * samples included; before the first sample mu = 0 and sigma = 0 (so the floor applies).
+ * state = {count, sum, sum of squares} carries the statistics across calls; fp64 throughout.
+ */
+int orc_shape_rewards(int stage, const unsigned char* feasible, const float* latency, const float* best_latency,
+                      int64_t M, int normalise, double sigma_min, double clip, double state[3], float* out) {
+    if ((stage != 0 && stage != 1) || M < 0 || (normalise && !(sigma_min > 0.0))) return 1;
+    for (int64_t j = 0; j < M; ++j) {
+        double raw;
+        if (!feasible[j]) raw = -1.0;
+        else if (stage == 0) raw = 1.0;
+        else raw = tanh(log((double)best_latency[j]) - log((double)latency[j]));
+        double r = raw;
+        if (normalise) {
+            double n = state[0];
+            double mu = n > 0.0 ? state[1] / n : 0.0;
+            double var = n > 0.0 ? state[2] / n - mu * mu : 0.0;
+            double sigma = var > 0.0 ? sqrt(var) : 0.0;
+            double denom = sigma > sigma_min ? sigma : sigma_min;
+            r = (raw - mu) / denom;
+            if (clip > 0.0) r = r > clip ? clip : (r < -clip ? -clip : r);
+            state[0] = n + 1.0;
+            state[1] += raw;
+            state[2] += raw * raw;
+        }
+        out[j] = (float)r;
+    }
+    return 0;
+}
+
 int orc_max_threads(void) {
 #ifdef _OPENMP
     return omp_get_max_threads();

@@ -50,6 +50,8 @@ def _load():
         L.orc_rerank_eps.argtypes = [i32p, f64p, C.c_int, f32p, C.c_double, C.c_int, C.c_float, C.c_uint64, C.c_uint64,
                                      C.c_uint32, i32p, f32p, f64p, u8p]
         L.orc_rerank_eps.restype = C.c_int
+        L.orc_shape_rewards.argtypes = [C.c_int, u8p, f32p, f32p, C.c_int64, C.c_int, C.c_double, C.c_double, f64p, f32p]
+        L.orc_shape_rewards.restype = C.c_int
         L.orc_update_q64.argtypes = [f32p, C.c_int64, i32p, f32p, C.c_int64, C.c_double]
         L.orc_update_q64.restype = C.c_int64
         L.orc_update_q32.argtypes = [f32p, C.c_int64, i32p, f32p, C.c_int64, C.c_float]
@@ -166,6 +168,21 @@ def rerank_eps(cand_ids, cand_sims, qtable, lam: float, k2: int, eps: float, see
     if rc:
         raise RuntimeError("orc_rerank_eps failed")
     return ids, s32, s64, ex
+
+
+def shape_rewards(stage: int, feasible, latency, best_latency, normalise: bool, sigma_min: float = 0.1,
+                  clip: float = 0.0, state=None):
+    """Stage rewards (Sec. 3.3 / 3.4) with optional online normalisation (App. A).  Returns (rewards f32,
+    new state [count, sum, sum of squares])."""
+    feasible = np.ascontiguousarray(feasible, np.uint8)
+    latency, best_latency = _f32(latency), _f32(best_latency)
+    st = np.zeros(3, np.float64) if state is None else np.ascontiguousarray(state, np.float64).copy()
+    out = np.empty(feasible.size, np.float32)
+    rc = _load().orc_shape_rewards(stage, _p(feasible, C.c_ubyte), _p(latency, C.c_float), _p(best_latency, C.c_float),
+                                   feasible.size, int(normalise), sigma_min, clip, _p(st, C.c_double), _p(out, C.c_float))
+    if rc:
+        raise RuntimeError("orc_shape_rewards failed")
+    return out, st
 
 
 def update_q64(qtable, ids, rewards, alpha: float):

@@ -454,3 +454,67 @@ def test_eps_planted_mistakes_are_caught(orc):
         differs_all |= wrong_all != list(got)
         differs_word |= wrong_word != list(got)
     assert differs_all and differs_word
+
+
+# ----------------------------------------------------------------------------- stage rewards and their normalisation
+
+def test_stage_rewards_closed_forms(orc):
+    rng = np.random.default_rng(8)
+    M = 2000
+    feas = (rng.random(M) < 0.7).astype(np.uint8)
+    lat = rng.uniform(0.1, 50, M).astype(np.float32)
+    best = rng.uniform(0.1, 50, M).astype(np.float32)
+    r1, _ = orc.shape_rewards(0, feas, lat, best, False)
+    assert np.array_equal(r1, np.where(feas, 1.0, -1.0).astype(np.float32))          # Sec. 3.3: binary feasibility reward
+    r2, _ = orc.shape_rewards(1, feas, lat, best, False)
+    rho = best.astype(np.float64) / lat.astype(np.float64)
+    closed = (rho * rho - 1) / (rho * rho + 1)          # tanh(ln rho) as a rational function: no tanh, no log
+    assert np.all(r2[feas == 0] == -1.0)
+    assert np.max(np.abs(r2[feas == 1] - closed[feas == 1])) < 1e-6
+    assert np.all(np.abs(r2[feas == 1]) < 1.0)                                        # App. A: tanh(log rho) in (-1, 1)
+    same, _ = orc.shape_rewards(1, np.ones(3, np.uint8), np.array([2.0, 5.0, 7.5], np.float32), np.array([2.0, 5.0, 7.5], np.float32), False)
+    assert np.all(same == 0.0)                                                        # no speed-up: reward 0
+    faster, _ = orc.shape_rewards(1, np.ones(2, np.uint8), np.array([1.0, 4.0], np.float32), np.array([2.0, 2.0], np.float32), False)
+    assert faster[0] > 0 > faster[1] and abs(faster[0] - 0.6) < 1e-7 and abs(faster[1] + 0.6) < 1e-7   # rho = 2, 1/2: 3/5
+
+
+def test_online_normalisation_against_numpy_prefix_statistics(orc):
+    rng = np.random.default_rng(9)
+    M = 600
+    feas = (rng.random(M) < 0.8).astype(np.uint8)
+    lat = rng.uniform(0.5, 5, M).astype(np.float32)
+    best = rng.uniform(0.5, 5, M).astype(np.float32)
+    raw, _ = orc.shape_rewards(1, feas, lat, best, False)
+    raw64 = np.where(feas, np.tanh(np.log(best.astype(np.float64)) - np.log(lat.astype(np.float64))), -1.0)
+    sigma_min = 0.05
+    got, state = orc.shape_rewards(1, feas, lat, best, True, sigma_min)
+    want = np.empty(M)
+    for t in range(M):
+        prev = raw64[:t]
+        mu = prev.mean() if t else 0.0
+        sd = prev.std() if t else 0.0                      # numpy's default is the population (1/t) form
+        want[t] = (raw64[t] - mu) / max(sd, sigma_min)
+    assert np.max(np.abs(got - want)) < 2e-5 * np.max(np.abs(want))
+    assert abs(state[0] - M) == 0 and abs(state[1] - raw64.sum()) < 1e-9 and abs(state[2] - (raw64 ** 2).sum()) < 1e-9
+    assert np.max(np.abs(got)) <= 2.0 / sigma_min + 1e-6                               # App. A: |R| <= 2 / sigma_min
+    assert abs(got[0] - raw[0] / sigma_min) < 1e-5                                     # first sample: mu = 0, floor applies
+    # the statistics used are the ones BEFORE the sample: a huge outlier does not normalise itself away
+    # splitting a batch in two calls with the state carried over changes nothing
+    a, st = orc.shape_rewards(1, feas[:250], lat[:250], best[:250], True, sigma_min)
+    b, st = orc.shape_rewards(1, feas[250:], lat[250:], best[250:], True, sigma_min, state=st)
+    assert np.array_equal(np.concatenate([a, b]), got) and np.array_equal(st, state)
+    # clipping
+    c, _ = orc.shape_rewards(1, feas, lat, best, True, sigma_min, clip=1.5)
+    assert np.array_equal(c, np.clip(got, -1.5, 1.5))
+
+
+def test_normalised_rewards_converge_to_the_z_score_map(orc):
+    """App. A, stability of online normalisation: for a stationary stream the map tends to (r - mu) / sigma."""
+    rng = np.random.default_rng(10)
+    M = 20000
+    lat = np.exp(rng.normal(0, 0.5, M)).astype(np.float32)
+    best = np.ones(M, np.float32)
+    raw = np.tanh(-np.log(lat.astype(np.float64)))
+    got, _ = orc.shape_rewards(1, np.ones(M, np.uint8), lat, best, True, 1e-3)
+    tail = slice(M - 2000, M)
+    assert np.max(np.abs(got[tail] - (raw[tail] - raw.mean()) / raw.std())) < 0.05
