@@ -145,6 +145,31 @@ int mem_size(const evomem_t* h, int64_t* n_out);
 /* Copy Q_stage[first .. first+n) into dst_dev (float[n]).  For tests and export. */
 int mem_read_q(evomem_t* h, int stage, int64_t first, int64_t n, float* dst_dev, void* hip_stream);
 
+/*
+ * Rewards of the two stages from verifier outcomes, ready for mem_update_q.
+ *   stage 0 (Sec. 3.3, cold-start drafting): +1 if feasible_dev[j] != 0, else -1; the latency
+ *           arrays are not read and may be NULL.
+ *   stage 1 (Sec. 3.4, continual refining): -1 if infeasible, else
+ *           tanh(log best_latency_dev[j] - log latency_dev[j])  (App. A: tanh(log rho)); latencies > 0.
+ * normalise != 0 applies the online normalisation of Sec. 3.4 / App. A in array order: sample j
+ * becomes (r_j - mu) / max(sigma, sigma_min), then is clipped to [-clip, clip] if clip > 0, where
+ * mu and sigma are the running mean and population deviation of all raw rewards of this stage seen
+ * BEFORE sample j (in earlier calls and earlier in this batch; before the first sample mu = 0 and
+ * sigma = 0).  The statistics are kept per stage in the workspace in fp64.
+ * rewards_out_dev: float[M].  M = 0 is a no-op.
+ * Errors: MEM_EINVAL (null pointers, stage, sigma_min <= 0 with normalise, clip < 0 or NaN), MEM_EHIP.
+ */
+int mem_shape_rewards(evomem_t* h, int stage, const unsigned char* feasible_dev, const float* latency_dev,
+                      const float* best_latency_dev, int64_t M, int normalise, float sigma_min, float clip,
+                      float* rewards_out_dev, void* hip_stream);
+
+/* Synchronises the device.  Running statistics of stage's raw rewards: how many, their mean and
+ * population deviation (App. A, running statistics). */
+int mem_reward_stats(evomem_t* h, int stage, double* count, double* mean, double* sigma);
+
+/* Forget the running statistics of a stage (asynchronous on the stream). */
+int mem_reward_stats_reset(evomem_t* h, int stage, void* hip_stream);
+
 /* Copy stored rows first .. first+n, widened to fp32 and un-tiled, into dst_dev (float[n][d]). */
 int mem_read_rows(evomem_t* h, int64_t first, int64_t n, float* dst_dev, void* hip_stream);
 

@@ -35,6 +35,10 @@ SYMBOLS = {
     "mem_retrieve_eps": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_float, C.c_float,
                                    C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                    C.c_void_p]),
+    "mem_shape_rewards": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_float,
+                                    C.c_float, C.c_void_p, C.c_void_p]),
+    "mem_reward_stats": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
+    "mem_reward_stats_reset": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p]),
     "mem_update_q": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_void_p, C.c_float, C.c_void_p]),
     "mem_size": (C.c_int, [C.c_void_p, C.POINTER(C.c_int64)]),
     "mem_read_q": (C.c_int, [C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p]),
@@ -174,6 +178,24 @@ class MemoryBank:
         assert ids.is_contiguous() and rewards.is_contiguous() and ids.numel() == rewards.numel()
         _check(self.lib.mem_update_q(self.h, _ptr(ids), ids.numel(), stage, _ptr(rewards), alpha, _stream()),
                "mem_update_q")
+
+    def shape_rewards(self, stage: int, feasible: torch.Tensor, latency=None, best_latency=None, normalise: bool = False,
+                      sigma_min: float = 0.1, clip: float = 0.0) -> torch.Tensor:
+        assert feasible.is_cuda and feasible.dtype == torch.uint8 and feasible.is_contiguous()
+        for t in (latency, best_latency):
+            assert t is None or (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and t.numel() == feasible.numel())
+        out = torch.empty(feasible.numel(), dtype=torch.float32, device=self.device)
+        _check(self.lib.mem_shape_rewards(self.h, stage, _ptr(feasible), _ptr(latency), _ptr(best_latency), feasible.numel(),
+                                          int(normalise), sigma_min, clip, _ptr(out), _stream()), "mem_shape_rewards")
+        return out
+
+    def reward_stats(self, stage: int):
+        n, mu, sd = C.c_double(), C.c_double(), C.c_double()
+        _check(self.lib.mem_reward_stats(self.h, stage, C.byref(n), C.byref(mu), C.byref(sd)), "mem_reward_stats")
+        return n.value, mu.value, sd.value
+
+    def reward_stats_reset(self, stage: int):
+        _check(self.lib.mem_reward_stats_reset(self.h, stage, _stream()), "mem_reward_stats_reset")
 
     def read_q(self, stage: int, first: int = 0, n: int | None = None) -> torch.Tensor:
         n = self.size() - first if n is None else n

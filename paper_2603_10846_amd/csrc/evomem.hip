@@ -14,6 +14,7 @@
 #include "k_scan_gemv.h"
 #include "k_scan_mfma.h"
 #include "k_select.h"
+#include "k_reward.h"
 #include "k_update.h"
 #include "layout.h"
 
@@ -203,6 +204,40 @@ int mem_profile_read(evomem_t* h, int capacity, int* n_out, float* ms_out, int64
     }
     *n_out = n;
     h->prof_n = 0;
+    return MEM_OK;
+}
+
+// the normaliser's statistics live in the zero-initialised counter block: double[2 stages][3] at byte 64
+static double* reward_state(evomem_t* h, int stage) { return reinterpret_cast<double*>(h->ws + h->w.counters + 64) + 3 * stage; }
+
+int mem_shape_rewards(evomem_t* h, int stage, const unsigned char* feasible_dev, const float* latency_dev,
+                      const float* best_latency_dev, int64_t M, int normalise, float sigma_min, float clip,
+                      float* rewards_out_dev, void* hip_stream) {
+    if (!h || (stage != 0 && stage != 1) || M < 0 || (normalise && !(sigma_min > 0.f)) || !(clip >= 0.f)) return MEM_EINVAL;
+    if (M == 0) return MEM_OK;
+    if (!feasible_dev || !rewards_out_dev || (stage == 1 && (!latency_dev || !best_latency_dev))) return MEM_EINVAL;
+    hipLaunchKernelGGL(k_shape_rewards, dim3(1), dim3(1024), 0, static_cast<hipStream_t>(hip_stream), stage, feasible_dev,
+                       latency_dev, best_latency_dev, M, normalise, (double)sigma_min, (double)clip, reward_state(h, stage),
+                       rewards_out_dev);
+    LAUNCHCHK();
+    return MEM_OK;
+}
+
+int mem_reward_stats(evomem_t* h, int stage, double* count, double* mean, double* sigma) {
+    if (!h || (stage != 0 && stage != 1) || !count || !mean || !sigma) return MEM_EINVAL;
+    double st[3];
+    HIPCHK(hipDeviceSynchronize());
+    HIPCHK(hipMemcpy(st, reward_state(h, stage), sizeof(st), hipMemcpyDeviceToHost));
+    *count = st[0];
+    *mean = st[0] > 0 ? st[1] / st[0] : 0.0;
+    const double var = st[0] > 0 ? st[2] / st[0] - (*mean) * (*mean) : 0.0;
+    *sigma = var > 0 ? sqrt(var) : 0.0;
+    return MEM_OK;
+}
+
+int mem_reward_stats_reset(evomem_t* h, int stage, void* hip_stream) {
+    if (!h || (stage != 0 && stage != 1)) return MEM_EINVAL;
+    HIPCHK(hipMemsetAsync(reward_state(h, stage), 0, 3 * sizeof(double), static_cast<hipStream_t>(hip_stream)));
     return MEM_OK;
 }
 

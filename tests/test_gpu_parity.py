@@ -405,3 +405,46 @@ def test_retrieve_eps_matches_oracle(orc, dtype, N, d, nq, k1, k2, eps):
     with pytest.raises(B.MemError):
         bank.retrieve_eps(_dev(q), stage, k1, k2, lam, 1.5, seed, step)
     bank.close()
+
+
+# ----------------------------------------------------------------------------- stage rewards (Sec. 3.3, 3.4, App. A)
+
+def test_stage_rewards_and_online_normalisation(orc):
+    rng = np.random.default_rng(108)
+    N = 4000
+    bank = _make_bank("f32", _unit(rng, N, 64), max_B=8, max_k1=16)
+    tol = lambda ref: 1e-6 * np.maximum(1.0, np.abs(ref))
+    state = [None, None]
+    for M in (1, 1023, 1024, 1025, 5000):           # pieces of 1024 inside the kernel: below, at, above, several
+        feas = (rng.random(M) < 0.75).astype(np.uint8)
+        lat = rng.uniform(0.2, 30, M).astype(np.float32)
+        best = rng.uniform(0.2, 30, M).astype(np.float32)
+        # stage 1 rewards: exact
+        r1 = bank.shape_rewards(0, _dev(feas)).cpu().numpy()
+        assert np.array_equal(r1, np.where(feas, 1.0, -1.0).astype(np.float32))
+        # stage 2 raw rewards
+        r2 = bank.shape_rewards(1, _dev(feas), _dev(lat), _dev(best)).cpu().numpy()
+        w2, _ = orc.shape_rewards(1, feas, lat, best, False)
+        assert np.all(np.abs(r2 - w2) <= tol(w2)) and np.all(r2[feas == 0] == -1.0)
+        # normalised, statistics carried from call to call (both stages keep their own)
+        for stage, clip in ((1, 0.0), (0, 2.5)):
+            got = bank.shape_rewards(stage, _dev(feas), _dev(lat), _dev(best), normalise=True, sigma_min=0.05, clip=clip)
+            want, state[stage] = orc.shape_rewards(stage, feas, lat, best, True, 0.05, clip, state=state[stage])
+            got = got.cpu().numpy()
+            assert np.all(np.abs(got - want) <= tol(want)), (M, stage, np.max(np.abs(got - want)))
+            n, mu, sd = bank.reward_stats(stage)
+            s = state[stage]
+            assert n == s[0] and abs(mu - s[1] / s[0]) < 1e-12 and abs(sd - np.sqrt(max(s[2] / s[0] - (s[1] / s[0]) ** 2, 0))) < 1e-9
+    # the rewards feed the value update: Q after the update is the sequential fp32 recurrence on them
+    ids = rng.integers(0, N, 5000).astype(np.int32)
+    rewards = bank.shape_rewards(1, _dev(feas), _dev(lat), _dev(best), normalise=True, sigma_min=0.05)
+    bank.update_q(_dev(ids), 1, rewards, 0.1)
+    want_q, _ = orc.update_q32(np.zeros(N, np.float32), ids, rewards.cpu().numpy(), 0.1)
+    assert np.array_equal(bank.read_q(1).cpu().numpy().view(np.uint32), want_q.view(np.uint32))
+    bank.reward_stats_reset(1)
+    assert bank.reward_stats(1) == (0.0, 0.0, 0.0) and bank.reward_stats(0)[0] > 0
+    with pytest.raises(B.MemError):
+        bank.shape_rewards(1, _dev(feas), _dev(lat), _dev(best), normalise=True, sigma_min=0.0)
+    with pytest.raises(B.MemError):
+        bank.shape_rewards(1, _dev(feas))            # stage 2 needs the latencies
+    bank.close()
