@@ -128,6 +128,30 @@ int mem_retrieve_eps(evomem_t* h, const float* queries_dev, int B, int stage, in
                      unsigned char* out_explored_dev, void* hip_stream);
 
 /*
+ * Typed / masked retrieval.  The bank of Sec. 3.2 holds items of several types (kernel code with
+ * its outcome, API templates, generation traces, summarised experience), and the generalisation
+ * study of Sec. 4.3 leaves the entries of held-out operators out of retrieval.  Every entry carries
+ * a 32-bit tag: type = tag & 0xff (types 0..31 can be retrieved), group = tag >> 8 (for instance the
+ * operator the entry stems from).
+ *   mem_attach_tags      hands the library a caller-owned device array uint32[capacity] for the tags;
+ *                        it is zero-filled (type 0, group 0) synchronously.  Needed once, before the
+ *                        two calls below (they return MEM_ESTATE otherwise).
+ *   mem_set_tags         copies n tags for entries first .. first+n-1 (which must exist) on the stream.
+ *   mem_retrieve_masked  as mem_retrieve, but query b only sees entries whose type bit is set in
+ *                        allow_types_dev[b] and whose group differs from exclude_group_dev[b]
+ *                        (0xffffffff excludes nothing): the pool is the top-k1 among those, and
+ *                        k1_eff = min(k1, number of such entries).  Both arrays are uint32[B].
+ * A query whose accepted entries are rare in the bank is still answered exactly, but slowly: the
+ * scan's threshold can only be as tight as the accepted entries of the sparsest pass allow.
+ */
+int mem_attach_tags(evomem_t* h, uint32_t* tags_dev);
+int mem_set_tags(evomem_t* h, int64_t first, int64_t n, const uint32_t* tags_dev, void* hip_stream);
+int mem_retrieve_masked(evomem_t* h, const float* queries_dev, int B, int stage, int k1, int k2, float lambda,
+                        const uint32_t* allow_types_dev, const uint32_t* exclude_group_dev,
+                        int32_t* out_ids_dev, float* out_scores_dev,
+                        int32_t* out_cand_ids_dev, float* out_cand_sims_dev, void* hip_stream);
+
+/*
  * Value update (Sec. 3.2, Eq. "unified update"): for j = 0..M-1 in array order,
  * Q_stage[ids[j]] <- Q + alpha (rewards[j] - Q), each operation rounded to fp32 (no fused
  * multiply-add).  An id that occurs several times receives its rewards one after another in array

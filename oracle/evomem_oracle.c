@@ -132,6 +132,43 @@ int orc_recall(const float* store, int64_t N, int d, int32_t id_base,
     return failed ? 2 : 0;
 }
 
+/*
+ * Typed / masked recall (Sec. 3.2: items of several types share the bank; Sec. 4.3: entries of held-out
+ * operators are left out).  tags[n]: type = tag & 0xff (only types 0..31 can be accepted), group =
+ * tag >> 8.  Query b accepts entry n iff bit `type` of allow[b] is set and group != exclude[b].
+ * The pool is the top-k1 of the accepted entries, by definition: every accepted pair is scored and
+ * all of them are sorted.
+ */
+int orc_recall_masked(const float* store, int64_t N, int d, const uint32_t* tags,
+                      const float* queries, int B, const uint32_t* allow, const uint32_t* exclude, int k1,
+                      int32_t* out_ids, double* out_sims) {
+    if (N < 0 || d <= 0 || B < 0 || k1 < 1) return 1;
+    pair_t* acc = (pair_t*)malloc(sizeof(pair_t) * (size_t)(N > 0 ? N : 1));
+    if (!acc) return 2;
+    for (int b = 0; b < B; ++b) {
+        const float* q = queries + (int64_t)b * d;
+        double invq = inv_norm(q, d);
+        int64_t m = 0;
+        for (int64_t n = 0; n < N; ++n) {
+            uint32_t type = tags[n] & 0xffu, group = tags[n] >> 8;
+            if (type > 31u || !((allow[b] >> type) & 1u) || group == exclude[b]) continue;
+            const float* e = store + n * d;
+            double dot = 0.0;
+            for (int i = 0; i < d; ++i) dot += (double)q[i] * (double)e[i];
+            acc[m].sim = dot * invq * inv_norm(e, d);
+            acc[m].id = (int32_t)n;
+            ++m;
+        }
+        qsort(acc, (size_t)m, sizeof(pair_t), pair_cmp);
+        for (int j = 0; j < k1; ++j) {
+            if (j < m) { out_ids[(int64_t)b * k1 + j] = acc[j].id; out_sims[(int64_t)b * k1 + j] = acc[j].sim; }
+            else       { out_ids[(int64_t)b * k1 + j] = -1;        out_sims[(int64_t)b * k1 + j] = -INFINITY; }
+        }
+    }
+    free(acc);
+    return 0;
+}
+
 /* Similarities of one query against a given list of ids (used to judge near-ties and to re-rank a
  * candidate set chosen by someone else). */
 int orc_sims_of(const float* store, int64_t N, int d, const float* query,

@@ -50,6 +50,8 @@ def _load():
         L.orc_rerank_eps.argtypes = [i32p, f64p, C.c_int, f32p, C.c_double, C.c_int, C.c_float, C.c_uint64, C.c_uint64,
                                      C.c_uint32, i32p, f32p, f64p, u8p]
         L.orc_rerank_eps.restype = C.c_int
+        L.orc_recall_masked.argtypes = [f32p, C.c_int64, C.c_int, u32p, f32p, C.c_int, u32p, u32p, C.c_int, i32p, f64p]
+        L.orc_recall_masked.restype = C.c_int
         L.orc_shape_rewards.argtypes = [C.c_int, u8p, f32p, f32p, C.c_int64, C.c_int, C.c_double, C.c_double, f64p, f32p]
         L.orc_shape_rewards.restype = C.c_int
         L.orc_update_q64.argtypes = [f32p, C.c_int64, i32p, f32p, C.c_int64, C.c_double]
@@ -140,6 +142,21 @@ def rerank(cand_ids, cand_sims, qtable, lam: float, k2: int):
     if rc:
         raise RuntimeError("orc_rerank failed")
     return ids, s32, s64
+
+
+def recall_masked(store, tags, queries, allow, exclude, k1: int):
+    """Top-k1 among the entries each query accepts (type bit set in allow[b], group != exclude[b])."""
+    store, queries = _f32(store), _f32(queries)
+    tags, allow, exclude = (np.ascontiguousarray(a, np.uint32) for a in (tags, allow, exclude))
+    B = queries.shape[0]
+    ids = np.empty((B, k1), np.int32)
+    sims = np.empty((B, k1), np.float64)
+    rc = _load().orc_recall_masked(_p(store, C.c_float), store.shape[0], store.shape[1], _p(tags, C.c_uint32),
+                                   _p(queries, C.c_float), B, _p(allow, C.c_uint32), _p(exclude, C.c_uint32), k1,
+                                   _p(ids, C.c_int32), _p(sims, C.c_double))
+    if rc:
+        raise RuntimeError("orc_recall_masked failed")
+    return ids, sims
 
 
 def philox4x32_10(ctr, key):

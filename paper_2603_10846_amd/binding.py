@@ -35,6 +35,10 @@ SYMBOLS = {
     "mem_retrieve_eps": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_float, C.c_float,
                                    C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                    C.c_void_p]),
+    "mem_attach_tags": (C.c_int, [C.c_void_p, C.c_void_p]),
+    "mem_set_tags": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p]),
+    "mem_retrieve_masked": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_float, C.c_void_p,
+                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "mem_shape_rewards": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_float,
                                     C.c_float, C.c_void_p, C.c_void_p]),
     "mem_reward_stats": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
@@ -107,6 +111,7 @@ class MemoryBank:
         if not torch.cuda.is_available():
             raise RuntimeError("evomem needs a GPU: there is no CPU path")
         self.lib, self.d, self.dtype, self.capacity = lib, d, DTYPES[dtype], capacity
+        self._tags = None
         self.device = torch.device(device)
         sb = lib.mem_store_bytes(d, self.dtype, capacity)
         wb = lib.mem_workspace_bytes(d, self.dtype, capacity, max_B, max_k1)
@@ -178,6 +183,29 @@ class MemoryBank:
         assert ids.is_contiguous() and rewards.is_contiguous() and ids.numel() == rewards.numel()
         _check(self.lib.mem_update_q(self.h, _ptr(ids), ids.numel(), stage, _ptr(rewards), alpha, _stream()),
                "mem_update_q")
+
+    def set_tags(self, first: int, tags: torch.Tensor):
+        """Tags of entries first..: an integer tensor of values < 2^32 (type = tag & 0xff, group = tag >> 8)."""
+        if self._tags is None:
+            self._tags = torch.empty(self.capacity, dtype=torch.int32, device=self.device)
+            _check(self.lib.mem_attach_tags(self.h, _ptr(self._tags)), "mem_attach_tags")
+        t = tags.to(device=self.device, dtype=torch.int64).to(torch.int32).contiguous()   # wraps to the 32-bit pattern
+        _check(self.lib.mem_set_tags(self.h, first, t.numel(), _ptr(t), _stream()), "mem_set_tags")
+
+    def retrieve_masked(self, queries: torch.Tensor, stage: int, k1: int, k2: int, lam: float, allow_types: torch.Tensor,
+                        exclude_group: torch.Tensor, want_candidates: bool = False):
+        assert queries.is_cuda and queries.dtype == torch.float32 and queries.is_contiguous()
+        B = queries.shape[0]
+        al = allow_types.to(device=self.device, dtype=torch.int64).to(torch.int32).contiguous()
+        ex = exclude_group.to(device=self.device, dtype=torch.int64).to(torch.int32).contiguous()
+        assert al.numel() == B and ex.numel() == B
+        ids = torch.empty((B, k2), dtype=torch.int32, device=self.device)
+        scores = torch.empty((B, k2), dtype=torch.float32, device=self.device)
+        cid = torch.empty((B, k1), dtype=torch.int32, device=self.device) if want_candidates else None
+        csim = torch.empty((B, k1), dtype=torch.float32, device=self.device) if want_candidates else None
+        _check(self.lib.mem_retrieve_masked(self.h, _ptr(queries), B, stage, k1, k2, lam, _ptr(al), _ptr(ex), _ptr(ids),
+                                            _ptr(scores), _ptr(cid), _ptr(csim), _stream()), "mem_retrieve_masked")
+        return ids, scores, cid, csim
 
     def shape_rewards(self, stage: int, feasible: torch.Tensor, latency=None, best_latency=None, normalise: bool = False,
                       sigma_min: float = 0.1, clip: float = 0.0) -> torch.Tensor:

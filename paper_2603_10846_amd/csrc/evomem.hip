@@ -70,6 +70,7 @@ struct evomem {
     // profiling
     bool prof_on;
     int prof_n;
+    uint32_t* tags = nullptr;   // per-entry tags of typed / masked retrieval (caller's buffer), or null
     std::vector<hipEvent_t> ev;
     std::vector<int64_t> prof_rows;
 };
@@ -287,11 +288,11 @@ std::vector<Level> plan_levels(int64_t N, int k1) {
     return lv;
 }
 
-template <int DT, int MQ, int WQ, int MR, int WR>
-int launch_mfma(evomem* h, hipStream_t st, int Bp, const Level& L, int k1) {
+template <int DT, int MQ, int WQ, int MR, int WR, bool MASKED>
+int launch_mfma(evomem* h, hipStream_t st, int Bp, const Level& L, int k1, const Mask& mask, int B) {
     constexpr int QT = 32 * MQ * WQ;
-    constexpr int lds = scan_mfma_lds_bytes<QT>();
-    auto kern = k_scan_mfma<DT, MQ, WQ, MR, WR>;
+    constexpr int lds = scan_mfma_lds_bytes<QT, MASKED>();
+    auto kern = k_scan_mfma<DT, MQ, WQ, MR, WR, MASKED>;
     static int resident[16] = {};          // workgroups of this kernel the whole device holds at once
     if (!resident[h->device & 15]) {
         HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds));
@@ -316,23 +317,29 @@ int launch_mfma(evomem* h, hipStream_t st, int Bp, const Level& L, int k1) {
     unsigned char* ws = h->ws;
     hipLaunchKernelGGL(kern, grid, block, lds, st, (const void*)h->store, (const float*)h->invnorm,
                        (const uint16_t*)(ws + h->w.qop), (const float*)(ws + h->w.invq), (const float*)(ws + h->w.thr),
-                       (uint32_t*)(ws + h->w.cnt), (uint64_t*)(ws + h->w.surv), h->N, h->nkb, Bp, L, flush_every);
+                       (uint32_t*)(ws + h->w.cnt), (uint64_t*)(ws + h->w.surv), h->N, h->nkb, Bp, L, flush_every, mask, B);
     LAUNCHCHK();
     return MEM_OK;
 }
 
-template <int DT>
-int launch_mfma_dt(evomem* h, hipStream_t st, int Bp, int qt, const Level& L, int k1) {
+template <int DT, bool MASKED>
+int launch_mfma_dt(evomem* h, hipStream_t st, int Bp, int qt, const Level& L, int k1, const Mask& mask, int B) {
     switch (qt) {
-        case 32: return launch_mfma<DT, 1, 1, 2, 4>(h, st, Bp, L, k1);
-        case 64: return launch_mfma<DT, 2, 1, 2, 4>(h, st, Bp, L, k1);
-        case 128: return launch_mfma<DT, 2, 2, 2, 4>(h, st, Bp, L, k1);     // 8 wavefronts, 64 x 64 each
-        default: return launch_mfma<DT, 4, 2, 2, 4>(h, st, Bp, L, k1);   // 8 wavefronts, 128 x 64 each
+        case 32: return launch_mfma<DT, 1, 1, 2, 4, MASKED>(h, st, Bp, L, k1, mask, B);
+        case 64: return launch_mfma<DT, 2, 1, 2, 4, MASKED>(h, st, Bp, L, k1, mask, B);
+        case 128: return launch_mfma<DT, 2, 2, 2, 4, MASKED>(h, st, Bp, L, k1, mask, B);   // 8 wavefronts, 64 x 64 each
+        default: return launch_mfma<DT, 4, 2, 2, 4, MASKED>(h, st, Bp, L, k1, mask, B);    // 8 wavefronts, 128 x 64 each
     }
+}
+template <bool MASKED>
+int launch_mfma_any(evomem* h, hipStream_t st, int Bp, int qt, const Level& L, int k1, const Mask& mask, int B) {
+    return h->dtype == MEM_F32 ? launch_mfma_dt<0, MASKED>(h, st, Bp, qt, L, k1, mask, B)
+         : h->dtype == MEM_BF16 ? launch_mfma_dt<1, MASKED>(h, st, Bp, qt, L, k1, mask, B)
+                                : launch_mfma_dt<2, MASKED>(h, st, Bp, qt, L, k1, mask, B);
 }
 
 template <int NB>
-int launch_gemv(evomem* h, hipStream_t st, int B, const Level& L) {
+int launch_gemv(evomem* h, hipStream_t st, int B, const Level& L, const Mask& mask) {
     unsigned char* ws = h->ws;
     dim3 grid((unsigned)L.ntiles), block(256);
     const float* invq = (const float*)(ws + h->w.invq);
@@ -342,13 +349,13 @@ int launch_gemv(evomem* h, hipStream_t st, int B, const Level& L) {
     uint64_t* surv = (uint64_t*)(ws + h->w.surv);
     if (h->dtype == MEM_F32)
         hipLaunchKernelGGL(k_scan_gemv32<NB>, grid, block, 0, st, (const float*)h->store, (const float*)h->invnorm, qf, invq,
-                           thr, cnt, surv, h->N, h->nkb, B, L);
+                           thr, cnt, surv, h->N, h->nkb, B, L, mask);
     else if (h->dtype == MEM_BF16)
         hipLaunchKernelGGL((k_scan_gemv16<BF16, NB>), grid, block, 0, st, (const uint16_t*)h->store, (const float*)h->invnorm,
-                           qf, invq, thr, cnt, surv, h->N, h->nkb, B, L);
+                           qf, invq, thr, cnt, surv, h->N, h->nkb, B, L, mask);
     else
         hipLaunchKernelGGL((k_scan_gemv16<F16, NB>), grid, block, 0, st, (const uint16_t*)h->store, (const float*)h->invnorm,
-                           qf, invq, thr, cnt, surv, h->N, h->nkb, B, L);
+                           qf, invq, thr, cnt, surv, h->N, h->nkb, B, L, mask);
     LAUNCHCHK();
     return MEM_OK;
 }
@@ -364,7 +371,7 @@ extern "C" int mem_plan_levels(int64_t N, int k1, int* stride, int* rho, int* nt
 
 static int retrieve_impl(evomem_t* h, const float* queries_dev, int B, int stage, int k1, int k2, float lambda,
                          int32_t* out_ids_dev, float* out_scores_dev, int32_t* out_cand_ids_dev,
-                         float* out_cand_sims_dev, void* hip_stream, const EpsGreedy& eg) {
+                         float* out_cand_sims_dev, void* hip_stream, const EpsGreedy& eg, const Mask& mask) {
     if (!h || B < 0 || B > h->max_B || (stage != 0 && stage != 1) || k1 < 1 || k2 < 1 || k2 > k1 || k1 > h->max_k1)
         return MEM_EINVAL;
     if (!(lambda >= 0.f && lambda <= 1.f)) return MEM_EINVAL;
@@ -416,14 +423,13 @@ static int retrieve_impl(evomem_t* h, const float* queries_dev, int B, int stage
             if (prof) HIPCHK(hipEventRecord(h->ev[2 * h->prof_n], st));
             int rc;
             if (gemv) {
-                rc = B == 1 ? launch_gemv<1>(h, st, B, L) : B == 2 ? launch_gemv<2>(h, st, B, L) : launch_gemv<4>(h, st, B, L);
+                rc = B == 1 ? launch_gemv<1>(h, st, B, L, mask) : B == 2 ? launch_gemv<2>(h, st, B, L, mask) : launch_gemv<4>(h, st, B, L, mask);
             } else {
                 // a sparse pass has few bank tiles: give each workgroup fewer queries, so that more
                 // workgroups share the pass and each one's k-loop is shorter
                 int lqt = qt;
                 while (lqt > 32 && (int64_t)L.ntiles * (Bp / lqt) < 128) lqt >>= 1;
-                rc = h->dtype == MEM_F32 ? launch_mfma_dt<0>(h, st, Bp, lqt, L, k1)
-                   : h->dtype == MEM_BF16 ? launch_mfma_dt<1>(h, st, Bp, lqt, L, k1) : launch_mfma_dt<2>(h, st, Bp, lqt, L, k1);
+                rc = mask.tags ? launch_mfma_any<true>(h, st, Bp, lqt, L, k1, mask, B) : launch_mfma_any<false>(h, st, Bp, lqt, L, k1, mask, B);
             }
             if (rc != MEM_OK) return rc;
             if (prof) {
@@ -431,7 +437,7 @@ static int retrieve_impl(evomem_t* h, const float* queries_dev, int B, int stage
                 int64_t rows = (int64_t)L.ntiles * TILE_ROWS;
                 h->prof_rows[h->prof_n++] = rows;
             }
-            hipLaunchKernelGGL(k_select, dim3(B), dim3(1024), 0, st, surv, cnt, thr, (const float*)invq, counters, k1, margin);
+            hipLaunchKernelGGL(k_select, dim3(B), dim3(1024), 0, st, surv, cnt, thr, (const float*)invq, counters, k1, margin, mask.tags != nullptr);
             LAUNCHCHK();
         }
         dim3 rgrid((unsigned)B);
@@ -455,7 +461,7 @@ extern "C" int mem_retrieve(evomem_t* h, const float* queries_dev, int B, int st
                             float* out_cand_sims_dev, void* hip_stream) {
     const EpsGreedy greedy{0, 0, 0, nullptr};
     return retrieve_impl(h, queries_dev, B, stage, k1, k2, lambda, out_ids_dev, out_scores_dev, out_cand_ids_dev,
-                         out_cand_sims_dev, hip_stream, greedy);
+                         out_cand_sims_dev, hip_stream, greedy, Mask{nullptr, nullptr, nullptr});
 }
 
 extern "C" int mem_retrieve_eps(evomem_t* h, const float* queries_dev, int B, int stage, int k1, int k2, float lambda,
@@ -465,7 +471,36 @@ extern "C" int mem_retrieve_eps(evomem_t* h, const float* queries_dev, int B, in
     if (!(eps >= 0.f && eps <= 1.f)) return MEM_EINVAL;
     const EpsGreedy eg{(uint64_t)((double)eps * 4294967296.0), seed, step, out_explored_dev};
     return retrieve_impl(h, queries_dev, B, stage, k1, k2, lambda, out_ids_dev, out_scores_dev, out_cand_ids_dev,
-                         out_cand_sims_dev, hip_stream, eg);
+                         out_cand_sims_dev, hip_stream, eg, Mask{nullptr, nullptr, nullptr});
+}
+
+extern "C" int mem_attach_tags(evomem_t* h, uint32_t* tags_dev) {
+    if (!h || !tags_dev) return MEM_EINVAL;
+    HIPCHK(hipMemset(tags_dev, 0, sizeof(uint32_t) * (size_t)h->capacity));
+    h->tags = tags_dev;
+    return MEM_OK;
+}
+
+extern "C" int mem_set_tags(evomem_t* h, int64_t first, int64_t n, const uint32_t* tags_dev, void* hip_stream) {
+    if (!h || first < 0 || n < 0 || first + n > h->N) return MEM_EINVAL;
+    if (!h->tags) return MEM_ESTATE;
+    if (n == 0) return MEM_OK;
+    if (!tags_dev) return MEM_EINVAL;
+    HIPCHK(hipMemcpyAsync(h->tags + first, tags_dev, sizeof(uint32_t) * (size_t)n, hipMemcpyDeviceToDevice,
+                          static_cast<hipStream_t>(hip_stream)));
+    return MEM_OK;
+}
+
+extern "C" int mem_retrieve_masked(evomem_t* h, const float* queries_dev, int B, int stage, int k1, int k2, float lambda,
+                                   const uint32_t* allow_types_dev, const uint32_t* exclude_group_dev,
+                                   int32_t* out_ids_dev, float* out_scores_dev, int32_t* out_cand_ids_dev,
+                                   float* out_cand_sims_dev, void* hip_stream) {
+    if (!h) return MEM_EINVAL;
+    if (!h->tags) return MEM_ESTATE;
+    if (B > 0 && (!allow_types_dev || !exclude_group_dev)) return MEM_EINVAL;
+    const EpsGreedy greedy{0, 0, 0, nullptr};
+    return retrieve_impl(h, queries_dev, B, stage, k1, k2, lambda, out_ids_dev, out_scores_dev, out_cand_ids_dev,
+                         out_cand_sims_dev, hip_stream, greedy, Mask{h->tags, allow_types_dev, exclude_group_dev});
 }
 
 extern "C" int mem_update_q(evomem_t* h, const int32_t* ids_dev, int64_t M, int stage, const float* rewards_dev,

@@ -27,7 +27,7 @@ __global__ __launch_bounds__(256) void k_scan_gemv16(const uint16_t* __restrict_
                                                      const float* __restrict__ qf, const float* __restrict__ invq,
                                                      const float* __restrict__ thr, uint32_t* __restrict__ cnt,
                                                      uint64_t* __restrict__ surv, int64_t N, int nkb, int B,
-                                                     Level L) {
+                                                     Level L, Mask mask) {
     const int tid = threadIdx.x, c = tid & 7, rbase = tid >> 3;   // rbase 0..31
     const int64_t t = level_tile(L, blockIdx.x);
     const int dpad = nkb * KB;
@@ -80,13 +80,15 @@ __global__ __launch_bounds__(256) void k_scan_gemv16(const uint16_t* __restrict_
         int64_t id = t * TILE_ROWS + i * 32 + rbase;
         if (id >= N) continue;
         float inve = invnorm[id];
+        const uint32_t tag = mask.tags ? mask.tags[id] : 0u;
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
             if (b >= B) break;
             float v = acc[i][b] * inve;
-            if (L.rho == 0)      // sparsest pass keeps every row at its own position, no counter
-                surv[(int64_t)b * SURV_CAP + (int64_t)blockIdx.x * TILE_ROWS + (id - t * TILE_ROWS)] = pack_key(v * invq[b], (int32_t)id);
-            else if (v >= thr[b]) append_survivor(v, invq[b], (int32_t)id, cnt + b, surv + (int64_t)b * SURV_CAP);
+            const bool ok = !mask.tags || eligible(tag, mask.allow[b], mask.exclude[b]);
+            if (L.rho == 0)      // sparsest pass keeps every row at its own position, no counter (0 = empty slot)
+                surv[(int64_t)b * SURV_CAP + (int64_t)blockIdx.x * TILE_ROWS + (id - t * TILE_ROWS)] = ok ? pack_key(v * invq[b], (int32_t)id) : 0ull;
+            else if (ok && v >= thr[b]) append_survivor(v, invq[b], (int32_t)id, cnt + b, surv + (int64_t)b * SURV_CAP);
         }
     }
 }
@@ -98,7 +100,7 @@ __global__ __launch_bounds__(256) void k_scan_gemv32(const float* __restrict__ s
                                                      const float* __restrict__ qf, const float* __restrict__ invq,
                                                      const float* __restrict__ thr, uint32_t* __restrict__ cnt,
                                                      uint64_t* __restrict__ surv, int64_t N, int nkb, int B,
-                                                     Level L) {
+                                                     Level L, Mask mask) {
     const int tid = threadIdx.x, c = tid & 15, rbase = tid >> 4;   // rbase 0..15
     const int64_t t = level_tile(L, blockIdx.x);
     const int dpad = nkb * KB;
@@ -140,13 +142,15 @@ __global__ __launch_bounds__(256) void k_scan_gemv32(const float* __restrict__ s
         int64_t id = t * TILE_ROWS + i * 16 + rbase;
         if (id >= N) continue;
         float inve = invnorm[id];
+        const uint32_t tag = mask.tags ? mask.tags[id] : 0u;
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
             if (b >= B) break;
             float v = acc[i][b] * inve;
-            if (L.rho == 0)      // sparsest pass keeps every row at its own position, no counter
-                surv[(int64_t)b * SURV_CAP + (int64_t)blockIdx.x * TILE_ROWS + (id - t * TILE_ROWS)] = pack_key(v * invq[b], (int32_t)id);
-            else if (v >= thr[b]) append_survivor(v, invq[b], (int32_t)id, cnt + b, surv + (int64_t)b * SURV_CAP);
+            const bool ok = !mask.tags || eligible(tag, mask.allow[b], mask.exclude[b]);
+            if (L.rho == 0)      // sparsest pass keeps every row at its own position, no counter (0 = empty slot)
+                surv[(int64_t)b * SURV_CAP + (int64_t)blockIdx.x * TILE_ROWS + (id - t * TILE_ROWS)] = ok ? pack_key(v * invq[b], (int32_t)id) : 0ull;
+            else if (ok && v >= thr[b]) append_survivor(v, invq[b], (int32_t)id, cnt + b, surv + (int64_t)b * SURV_CAP);
         }
     }
 }

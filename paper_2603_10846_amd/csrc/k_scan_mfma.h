@@ -74,18 +74,20 @@ constexpr int SCAN_LIST_CAP = 2048;     // survivor entries a workgroup can stag
 
 // LDS: two stages (bank tile + query tile); per-query threshold, inverse norm, survivor count and
 // list base; the workgroup's survivor list (8-byte key + 4-byte query index per entry); a counter.
-template <int QT> constexpr int scan_mfma_lds_bytes() {
-    return 2 * (STAGE_BANK_BYTES + QT * 128) + QT * 16 + SCAN_LIST_CAP * 12 + 16;
+// (masked variant: the per-query type masks and excluded groups in addition)
+template <int QT, bool MASKED = false> constexpr int scan_mfma_lds_bytes() {
+    return 2 * (STAGE_BANK_BYTES + QT * 128) + QT * 16 + SCAN_LIST_CAP * 12 + 16 + (MASKED ? QT * 8 : 0);
 }
 
 // DT: 0 fp32 store (bf16 split), 1 bf16, 2 f16.  Wave grid WQ x WR, each wave MQ x MR blocks of 32x32.
 // gridDim.x is a multiple of 8 * (Bp / QT).
-template <int DT, int MQ, int WQ, int MR, int WR>
+// MASKED: typed / masked retrieval -- a row is kept for a query only if the query accepts its tag.
+template <int DT, int MQ, int WQ, int MR, int WR, bool MASKED>
 __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restrict__ store_, const float* __restrict__ invnorm,
                                                    const uint16_t* __restrict__ qop, const float* __restrict__ invq,
                                                    const float* __restrict__ thr, uint32_t* __restrict__ cnt,
                                                    uint64_t* __restrict__ surv, int64_t N, int nkb, int Bp,
-                                                   Level L, int flush_every) {
+                                                   Level L, int flush_every, Mask mask, int B) {
     static_assert((WQ * WR == 4 || WQ * WR == 8) && MR * WR == 8, "4 or 8 waves, 256 bank rows per workgroup");
     constexpr int NT = 64 * WQ * WR;                   // lanes per workgroup
     constexpr int QT = 32 * MQ * WQ;
@@ -133,12 +135,18 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
     uint64_t* lkey = reinterpret_cast<uint64_t*>(base_s + QT);
     uint32_t* lq = reinterpret_cast<uint32_t*>(lkey + SCAN_LIST_CAP);
     uint32_t* total_s = lq + SCAN_LIST_CAP;
+    uint32_t* allow_s = total_s + 4;                    // masked variant only
+    uint32_t* exclude_s = allow_s + QT;
     for (int i = tid; i < QT; i += NT) {
         const float th = thr[q0 + i];
         const uint16_t hi = enc16(th), lo = enc16(th - dec16(hi));
         thp_s[i] = hi | ((uint32_t)lo << 16);
         invq_s[i] = invq[q0 + i];
         cnt_s[i] = 0;
+        if constexpr (MASKED) {                         // padding queries accept nothing
+            allow_s[i] = q0 + i < B ? mask.allow[q0 + i] : 0u;
+            exclude_s[i] = q0 + i < B ? mask.exclude[q0 + i] : 0u;
+        }
     }
     if (tid == 0) *total_s = 0;
 
@@ -373,6 +381,7 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
         const uint32_t total = *total_s < (uint32_t)SCAN_LIST_CAP ? *total_s : (uint32_t)SCAN_LIST_CAP;
         for (uint32_t e = tid; e < total; e += NT) {
             uint32_t ql = lq[e];
+            if (MASKED && ql == 0xffffu) continue;            // a survivor its query does not accept
             lq[e] = ql | (atomicAdd(cnt_s + ql, 1u) << 16);   // rank among the staged entries of ql
         }
         __syncthreads();
@@ -395,7 +404,7 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 const uint32_t e = e0 + k * NT;
-                if (e < total) {
+                if (e < total && !(MASKED && (lq[e] & 0xffffu) == 0xffffu)) {
                     const uint32_t ql = lq[e] & 0xffffu, rank = lq[e] >> 16;
                     const uint32_t pos = base_s[ql] + rank;
                     if (pos < (uint32_t)SURV_CAP)
@@ -459,6 +468,8 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
                 const int64_t id = t * TILE_ROWS + rt;
                 if (id < N) {
                     const float inve = invnorm[id];
+                    uint32_t tag = 0;
+                    if constexpr (MASKED) tag = mask.tags[id];
                     const int64_t pos = (int64_t)j * TILE_ROWS + rt;
 #pragma unroll
                     for (int a = 0; a < MQ; ++a) {
@@ -467,7 +478,8 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
 #pragma unroll
                         for (int r = 0; r < 16; ++r) {
                             const int ql = (wq_u * MQ + a) * 32 + 4 * (half + opq) + 8 * (r >> 2) + (r & 3);
-                            surv[(int64_t)(q0 + ql) * SURV_CAP + pos] = pack_key(acc[a][b][r] * inve * invq_s[ql], (int32_t)id);
+                            const bool ok = !MASKED || eligible(tag, allow_s[ql], exclude_s[ql]);
+                            surv[(int64_t)(q0 + ql) * SURV_CAP + pos] = ok ? pack_key(acc[a][b][r] * inve * invq_s[ql], (int32_t)id) : 0ull;   // 0 = empty slot
                         }
                         __builtin_amdgcn_sched_barrier(0);
                     }
@@ -527,10 +539,12 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
                     const int ln = fresh_lane(), half = ln >> 5, l32 = ln & 31;
                     const int32_t id = (int32_t)(t * TILE_ROWS + (wr_u * MR + b) * 32 + l32);
                     const int ql = (wq_u * MQ + a) * 32 + 4 * half + 8 * ((r >> 2) & 3) + (r & 3);
+                    bool ok = true;
+                    if constexpr (MASKED) ok = eligible(mask.tags[id], allow_s[ql], exclude_s[ql]);
                     if (slot < (uint32_t)SCAN_LIST_CAP) {
                         lkey[slot] = ((uint64_t)__float_as_uint(av) << 32) | (uint32_t)id;
-                        lq[slot] = (uint32_t)ql;
-                    } else {   // list full (a very loose threshold): fall back to the direct path
+                        lq[slot] = ok ? (uint32_t)ql : 0xffffu;          // the slot was reserved before the check
+                    } else if (ok) {   // list full (a very loose threshold): fall back to the direct path
                         uint32_t pos = atomicAdd(cnt + q0 + ql, 1u);
                         if (pos < (uint32_t)SURV_CAP) surv[(int64_t)(q0 + ql) * SURV_CAP + pos] = finish_key(av, ql, id, invnorm[id]);
                     }

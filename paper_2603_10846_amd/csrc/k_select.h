@@ -40,7 +40,7 @@ __device__ __forceinline__ void bitonic_desc(T* a, int n, int tid, int nthreads,
 // histograms in LDS, sums them, and one wavefront picks the digit by a suffix scan.
 __global__ __launch_bounds__(1024) void k_select(uint64_t* __restrict__ surv, uint32_t* __restrict__ cnt,
                                                  float* __restrict__ thr, const float* __restrict__ invq,
-                                                 uint32_t* __restrict__ counters, int k1, float margin) {
+                                                 uint32_t* __restrict__ counters, int k1, float margin, int may_have_empty) {
     __shared__ uint32_t hist[16][256];
     __shared__ uint32_t tot[256];
     __shared__ uint64_t pivot_s;
@@ -50,7 +50,7 @@ __global__ __launch_bounds__(1024) void k_select(uint64_t* __restrict__ surv, ui
     const uint32_t raw = cnt[b];
     const int n = raw > (uint32_t)SURV_CAP ? SURV_CAP : (int)raw;
     if (raw > (uint32_t)SURV_CAP && tid == 0) atomicAdd(counters + 1, 1u);
-    if (n < k1) {                       // fewer rows than the pool size: keep them all, no threshold
+    if (!may_have_empty && n < k1) {    // fewer rows than the pool size: keep them all, no threshold
         if (tid == 0) { cnt[b] = (uint32_t)n; thr[b] = -2.0f / invq[b]; }   // finite floor, see k_prep_queries
         return;
     }
@@ -58,6 +58,29 @@ __global__ __launch_bounds__(1024) void k_select(uint64_t* __restrict__ surv, ui
 #pragma unroll
     for (int i = 0; i < 8; ++i) { int idx = i * 1024 + tid; key[i] = idx < n ? list[idx] : 0ull; }   // 0 = empty
     if (tid == 0) { band_s = 0; nout_s = 0; }
+    if (may_have_empty) {               // uniform
+        // A masked sparsest pass leaves the slots of rows the query does not accept empty (key 0): if
+        // fewer than k1 slots are in use, keep those (compacted to the head of the list), no threshold.
+        uint32_t used = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) used += key[i] != 0;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) used += __shfl_xor(used, o, 64);
+        __syncthreads();
+        if (lane == 0 && used) atomicAdd(&band_s, used);
+        __syncthreads();
+        if (band_s < (uint32_t)k1) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                if (key[i] != 0) list[atomicAdd(&nout_s, 1u)] = key[i];
+            __syncthreads();
+            if (tid == 0) { cnt[b] = nout_s; thr[b] = -2.0f / invq[b]; }
+            return;
+        }
+        __syncthreads();
+        if (tid == 0) band_s = 0;
+        __syncthreads();
+    }
     uint64_t prefix = 0, pivot = 0;
     uint32_t need = (uint32_t)k1;
     for (int pass = 0; pass < 8; ++pass) {

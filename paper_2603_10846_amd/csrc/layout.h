@@ -83,6 +83,19 @@ struct Level {
     int rho;        // parent stride / S  (0 for the sparsest level)
     int ntiles;     // tiles this level scans
 };
+// Typed / masked retrieval (Sec. 3.2: the bank holds items of several types; Sec. 4.3: entries that
+// stem from held-out operators are excluded).  Every entry carries a 32-bit tag: type = tag & 0xff
+// (types 0..31), group = tag >> 8.  A query names the types it accepts as a bit mask and at most one
+// group to leave out (0xffffffff: none).  tags == nullptr means no filtering.
+struct Mask {
+    const uint32_t* tags;      // [capacity]
+    const uint32_t* allow;     // [B] bit t set = type t accepted
+    const uint32_t* exclude;   // [B] group to leave out
+};
+__host__ __device__ __forceinline__ bool eligible(uint32_t tag, uint32_t allow, uint32_t exclude) {
+    return ((allow >> (tag & 31u)) & 1u) != 0 && (tag & 0xe0u) == 0 && (tag >> 8) != exclude;
+}
+
 __host__ __device__ __forceinline__ int64_t level_tile(const Level& L, int j) {
     int64_t u = L.rho ? ((int64_t)(j / (L.rho - 1)) * L.rho + (j % (L.rho - 1)) + 1) : j;
     return u * L.stride;

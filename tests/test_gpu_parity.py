@@ -448,3 +448,71 @@ def test_stage_rewards_and_online_normalisation(orc):
     with pytest.raises(B.MemError):
         bank.shape_rewards(1, _dev(feas))            # stage 2 needs the latencies
     bank.close()
+
+
+# ----------------------------------------------------------------------------- typed / masked retrieval
+
+def _check_masked(orc, bank, dtype, rows, q, tags, allow, exclude, qtab, stage, k1, k2, lam):
+    ids, sc, cid, csim = bank.retrieve_masked(_dev(q), stage, k1, k2, lam, torch.from_numpy(allow.astype(np.int64)),
+                                              torch.from_numpy(exclude.astype(np.int64)), want_candidates=True)
+    torch.cuda.synchronize()
+    gpu = {"ids": ids.cpu().numpy(), "scores": sc.cpu().numpy(), "cand_ids": cid.cpu().numpy(), "cand_sims": csim.cpu().numpy()}
+    st, qr = orc.round_to_store(rows, DT[dtype]), orc.round_to_store(q, DT[dtype])
+    types, groups = tags & 0xff, tags >> 8
+    total = {"queries": 0, "boundary_swaps": 0}
+    for b in range(len(q)):
+        keep = np.flatnonzero((types < 32) & ((allow[b] >> (types & 31)) & 1).astype(bool) & (groups != exclude[b]))
+        # the pool may only hold accepted entries ...
+        pool = gpu["cand_ids"][b]
+        assert set(pool[pool >= 0].tolist()) <= set(keep.tolist()), f"query {b}: pool holds entries it does not accept"
+        # ... and must be the oracle's masked top-k1: compare on the sub-bank of accepted entries (ids mapped)
+        if len(keep) == 0:
+            assert np.all(pool == -1) and np.all(gpu["ids"][b] == -1)
+            continue
+        back = {int(g): i for i, g in enumerate(keep)}
+        sub = {"cand_ids": np.array([[back.get(int(i), -1) for i in pool]], np.int32), "cand_sims": gpu["cand_sims"][b:b + 1],
+               "ids": np.array([[back.get(int(i), -1) for i in gpu["ids"][b]]], np.int32), "scores": gpu["scores"][b:b + 1]}
+        s = parity.check_retrieve(orc, np.ascontiguousarray(st[keep]), qr[b:b + 1], qtab[stage][keep], k1, k2, lam, sub)
+        total["queries"] += 1
+        total["boundary_swaps"] += s["boundary_swaps"]
+    # the oracle's own masked recall agrees too (ids, up to boundary near-ties already judged above)
+    o_ids, _ = orc.recall_masked(st, tags, qr, allow, exclude, k1)
+    if total["boundary_swaps"] == 0:
+        assert np.array_equal(np.sort(o_ids, axis=1), np.sort(gpu["cand_ids"], axis=1))
+    return total
+
+
+@pytest.mark.parametrize("dtype,N,d,nq", [("f32", 5000, 96, 3), ("bf16", 30000, 256, 70), ("f16", 12000, 128, 200), ("bf16", 9000, 64, 1)])
+def test_masked_retrieval_matches_oracle(orc, dtype, N, d, nq):
+    rng = np.random.default_rng(N + nq)
+    rows, q = _unit(rng, N, d), _unit(rng, nq, d)
+    qtab = rng.uniform(-1, 1, (2, N)).astype(np.float32)
+    types = rng.choice(4, N, p=[0.55, 0.3, 0.13, 0.02]).astype(np.uint32)      # type 3 is rare
+    groups = rng.integers(0, 40, N).astype(np.uint32)
+    tags = types | (groups << 8)
+    bank = _make_bank(dtype, rows, qtab, max_B=256)
+    # before tags are attached the call is refused
+    with pytest.raises(B.MemError) as e:
+        bank.retrieve_masked(_dev(q), 0, 8, 2, 0.5, torch.zeros(nq, dtype=torch.int64), torch.zeros(nq, dtype=torch.int64))
+    assert e.value.status == B.MEM_ESTATE
+    bank.set_tags(0, torch.from_numpy(tags[:N // 2].astype(np.int64)))
+    bank.set_tags(N // 2, torch.from_numpy(tags[N // 2:].astype(np.int64)))
+    allow = rng.choice([0b0001, 0b0010, 0b0011, 0b0100, 0b1111, 0b1000], nq).astype(np.uint32)
+    exclude = np.where(rng.random(nq) < 0.5, rng.integers(0, 40, nq), 0xffffffff).astype(np.uint32)
+    k1, k2 = (64, 8) if nq > 1 else (32, 4)
+    got = _check_masked(orc, bank, dtype, rows, q, tags, allow, exclude, qtab, 1, k1, k2, 0.5)
+    assert got["queries"] == nq
+    # accepting everything reproduces the plain call bit for bit
+    plain = parity.gpu_retrieve(bank, torch, q, 1, k1, k2, 0.5)
+    ids, sc, cid, csim = bank.retrieve_masked(_dev(q), 1, k1, k2, 0.5, torch.full((nq,), 0xffffffff, dtype=torch.int64),
+                                              torch.full((nq,), 0xffffffff, dtype=torch.int64), want_candidates=True)
+    assert np.array_equal(cid.cpu().numpy(), plain["cand_ids"]) and np.array_equal(ids.cpu().numpy(), plain["ids"])
+    assert np.array_equal(sc.cpu().numpy().view(np.uint32), plain["scores"].view(np.uint32))
+    # a query that accepts nothing, and one whose accepted entries are fewer than k1
+    few = np.zeros(N, np.uint32)
+    few[rng.permutation(N)[:10]] = 5
+    bank.set_tags(0, torch.from_numpy(few.astype(np.int64)))
+    allow2 = np.array([0, 1 << 5] + [1] * (nq - 2), np.uint32)[:nq] if nq >= 2 else np.array([1 << 5], np.uint32)
+    got = _check_masked(orc, bank, dtype, rows, q, few, allow2, np.full(nq, 0xffffffff, np.uint32), qtab, 0, k1, k2, 0.5)
+    assert bank.counters() == (0, 0)
+    bank.close()

@@ -518,3 +518,36 @@ def test_normalised_rewards_converge_to_the_z_score_map(orc):
     got, _ = orc.shape_rewards(1, np.ones(M, np.uint8), lat, best, True, 1e-3)
     tail = slice(M - 2000, M)
     assert np.max(np.abs(got[tail] - (raw[tail] - raw.mean()) / raw.std())) < 0.05
+
+
+# ----------------------------------------------------------------------------- typed / masked recall
+
+def test_masked_recall_equals_recall_on_the_accepted_sub_bank(orc):
+    """Pin: leaving entries out must be the same as a bank that never held them (ids mapped back)."""
+    rng = np.random.default_rng(11)
+    N, d = 700, 24
+    rows = _unit(rng, N, d)
+    q = _unit(rng, 6, d)
+    types = rng.integers(0, 4, N).astype(np.uint32)
+    groups = rng.integers(0, 9, N).astype(np.uint32)
+    tags = types | (groups << 8)
+    allow = np.array([0b0001, 0b0110, 0b1111, 0b1000, 0b1111, 0], np.uint32)
+    exclude = np.array([0xffffffff, 3, 0xffffffff, 5, 8, 0xffffffff], np.uint32)
+    ids, sims = orc.recall_masked(rows, tags, q, allow, exclude, 20)
+    for b in range(6):
+        keep = np.flatnonzero(((allow[b] >> types) & 1).astype(bool) & (groups != exclude[b]))
+        if len(keep) == 0:
+            assert np.all(ids[b] == -1) and np.all(np.isneginf(sims[b]))
+            continue
+        sub_ids, sub_sims = orc.recall(np.ascontiguousarray(rows[keep]), q[b:b + 1], 20)
+        live = sub_ids[0] >= 0
+        assert np.array_equal(ids[b][live], keep[sub_ids[0][live]]) and np.array_equal(sims[b][live], sub_sims[0][live])
+        assert np.all(ids[b][~live] == -1)
+    # accepting everything is the plain recall; types above 31 are never retrievable
+    all_ids, all_sims = orc.recall_masked(rows, tags, q, np.full(6, 0xffffffff, np.uint32), np.full(6, 0xffffffff, np.uint32), 20)
+    p_ids, p_sims = orc.recall(rows, q, 20)
+    assert np.array_equal(all_ids, p_ids) and np.array_equal(all_sims, p_sims)
+    odd = tags.copy()
+    odd[:350] = 40 | (groups[:350] << 8)
+    o_ids, _ = orc.recall_masked(rows, odd, q, np.full(6, 0xffffffff, np.uint32), np.full(6, 0xffffffff, np.uint32), 20)
+    assert o_ids.min() >= 350
