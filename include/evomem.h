@@ -53,7 +53,7 @@ enum mem_status {
 enum mem_dtype { MEM_F32 = 0, MEM_BF16 = 1, MEM_F16 = 2 }; /* storage element type */
 enum mem_stage { MEM_STAGE_DRAFT = 0, MEM_STAGE_REFINE = 1 }; /* Q_1 / Q_2 of Sec. 3.2 */
 
-#define MEM_MAX_K1 256   /* largest candidate pool */
+#define MEM_MAX_K1 2048  /* largest candidate pool (Sec. 4.4 studies pools of 3x to 30x the final count) */
 #define MEM_MAX_B 4096   /* largest query batch per call */
 
 /* Bytes the caller must allocate for the embedding store (tiled layout, padded), for given

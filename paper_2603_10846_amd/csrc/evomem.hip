@@ -14,13 +14,14 @@
 #include "k_scan_gemv.h"
 #include "k_scan_mfma.h"
 #include "k_select.h"
+#include "k_rerank_big.h"
 #include "k_reward.h"
 #include "k_update.h"
 #include "layout.h"
 
 using namespace evk;
 
-static_assert(MEM_MAX_K1 == MEM_MAX_K1_INTERNAL, "header and kernels disagree on the largest pool");
+static_assert(MEM_MAX_K1 == evk::BIG_K1_MAX, "header and kernels disagree on the largest pool");
 
 namespace {
 
@@ -33,7 +34,7 @@ struct Workspace {   // byte offsets into the caller's workspace
     size_t counters, qf, qop, invq, invq64, thr, cnt, surv, exact, total;
 };
 
-Workspace carve(int d, int dtype, int max_B) {
+Workspace carve(int d, int dtype, int max_B, int max_k1) {
     const int64_t dpad = round_up(d, KB), Bp = round_up(max_B, 256);
     Workspace w{};
     size_t o = 0;
@@ -46,7 +47,7 @@ Workspace carve(int d, int dtype, int max_B) {
     w.thr = take((size_t)Bp * 4);
     w.cnt = take((size_t)Bp * 4);
     w.surv = take((size_t)Bp * SURV_CAP * 8);
-    w.exact = take((size_t)Bp * KEEP_MAX * 8);
+    w.exact = take((size_t)Bp * keep_of(max_k1) * 8);
     w.total = o;
     return w;
 }
@@ -87,7 +88,7 @@ size_t mem_store_bytes(int d, int dtype, int64_t capacity) {
 
 size_t mem_workspace_bytes(int d, int dtype, int64_t capacity, int max_B, int max_k1) {
     if (!shape_ok(d, dtype, capacity) || max_B < 1 || max_B > MEM_MAX_B || max_k1 < 1 || max_k1 > MEM_MAX_K1) return 0;
-    return carve(d, dtype, max_B).total;
+    return carve(d, dtype, max_B, max_k1).total;
 }
 
 int mem_create(evomem_t** out, int d, int dtype, int64_t capacity, void* store_dev, float* invnorm_dev,
@@ -97,7 +98,7 @@ int mem_create(evomem_t** out, int d, int dtype, int64_t capacity, void* store_d
     if (!shape_ok(d, dtype, capacity) || !store_dev || !invnorm_dev || !q_dev || !workspace_dev) return MEM_EINVAL;
     if (max_B < 1 || max_B > MEM_MAX_B || max_k1 < 1 || max_k1 > MEM_MAX_K1 || device < 0) return MEM_EINVAL;
     if (((uintptr_t)store_dev | (uintptr_t)workspace_dev) & 255) return MEM_EINVAL;
-    Workspace w = carve(d, dtype, max_B);
+    Workspace w = carve(d, dtype, max_B, max_k1);
     if (workspace_bytes < w.total) return MEM_EWORKSPACE;
     evomem* h = new (std::nothrow) evomem();
     if (!h) return MEM_EHIP;
@@ -392,6 +393,7 @@ static int retrieve_impl(evomem_t* h, const float* queries_dev, int B, int stage
     uint32_t* cnt = (uint32_t*)(ws + h->w.cnt);
     uint64_t* surv = (uint64_t*)(ws + h->w.surv);
     double* exact = (double*)(ws + h->w.exact);
+    const int exact_stride = keep_of(h->max_k1);
     uint32_t* counters = (uint32_t*)(ws + h->w.counters);
 
     std::vector<Level> levels;
@@ -437,21 +439,36 @@ static int retrieve_impl(evomem_t* h, const float* queries_dev, int B, int stage
                 int64_t rows = (int64_t)L.ntiles * TILE_ROWS;
                 h->prof_rows[h->prof_n++] = rows;
             }
-            hipLaunchKernelGGL(k_select, dim3(B), dim3(1024), 0, st, surv, cnt, thr, (const float*)invq, counters, k1, margin, mask.tags != nullptr);
+            hipLaunchKernelGGL(k_select, dim3(B), dim3(1024), 0, st, surv, cnt, thr, (const float*)invq, counters, k1, margin, mask.tags != nullptr, keep_of(k1));
             LAUNCHCHK();
         }
         dim3 rgrid((unsigned)B);
         if (h->dtype == MEM_F32)
-            hipLaunchKernelGGL(k_rescore<0>, rgrid, dim3(1024), 0, st, (const void*)h->store, (const float*)qf, (const double*)invq64, (const uint64_t*)surv, (const uint32_t*)cnt, exact, h->nkb);
+            hipLaunchKernelGGL(k_rescore<0>, rgrid, dim3(1024), 0, st, (const void*)h->store, (const float*)qf, (const double*)invq64, (const uint64_t*)surv, (const uint32_t*)cnt, exact, h->nkb, exact_stride);
         else if (h->dtype == MEM_BF16)
-            hipLaunchKernelGGL(k_rescore<1>, rgrid, dim3(1024), 0, st, (const void*)h->store, (const float*)qf, (const double*)invq64, (const uint64_t*)surv, (const uint32_t*)cnt, exact, h->nkb);
+            hipLaunchKernelGGL(k_rescore<1>, rgrid, dim3(1024), 0, st, (const void*)h->store, (const float*)qf, (const double*)invq64, (const uint64_t*)surv, (const uint32_t*)cnt, exact, h->nkb, exact_stride);
         else
-            hipLaunchKernelGGL(k_rescore<2>, rgrid, dim3(1024), 0, st, (const void*)h->store, (const float*)qf, (const double*)invq64, (const uint64_t*)surv, (const uint32_t*)cnt, exact, h->nkb);
+            hipLaunchKernelGGL(k_rescore<2>, rgrid, dim3(1024), 0, st, (const void*)h->store, (const float*)qf, (const double*)invq64, (const uint64_t*)surv, (const uint32_t*)cnt, exact, h->nkb, exact_stride);
         LAUNCHCHK();
     }
-    hipLaunchKernelGGL(k_rerank, dim3(B), dim3(RERANK_T), 0, st, (const uint64_t*)surv, (const uint32_t*)cnt, (const double*)exact,
-                       (const float*)(h->q + (int64_t)stage * h->capacity), k1, k2, (double)lambda, out_ids_dev, out_scores_dev,
-                       out_cand_ids_dev, out_cand_sims_dev, eg);
+    if (k1 <= MEM_MAX_K1_INTERNAL) {
+        hipLaunchKernelGGL(k_rerank, dim3(B), dim3(RERANK_T), 0, st, (const uint64_t*)surv, (const uint32_t*)cnt, (const double*)exact,
+                           (const float*)(h->q + (int64_t)stage * h->capacity), k1, k2, (double)lambda, out_ids_dev, out_scores_dev,
+                           out_cand_ids_dev, out_cand_sims_dev, eg, exact_stride);
+    } else {                               // large pools: sorts instead of counting ranks
+        int cap = 2;
+        while (cap < keep_of(k1)) cap <<= 1;
+        const size_t lds = rerank_big_lds(cap, k1, k2);
+        static bool lds_set[16] = {};
+        if (!lds_set[h->device & 15]) {
+            HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void*>(k_rerank_big), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)rerank_big_lds(4096, BIG_K1_MAX, BIG_K1_MAX)));
+            lds_set[h->device & 15] = true;
+        }
+        hipLaunchKernelGGL(k_rerank_big, dim3(B), dim3(BIG_T), lds, st, (const uint64_t*)surv, (const uint32_t*)cnt,
+                           (const double*)exact, exact_stride, (const float*)(h->q + (int64_t)stage * h->capacity), k1, k2,
+                           (double)lambda, cap, out_ids_dev, out_scores_dev, out_cand_ids_dev, out_cand_sims_dev, eg);
+    }
     LAUNCHCHK();
     return MEM_OK;
 }

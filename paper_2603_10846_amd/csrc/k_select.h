@@ -40,7 +40,7 @@ __device__ __forceinline__ void bitonic_desc(T* a, int n, int tid, int nthreads,
 // histograms in LDS, sums them, and one wavefront picks the digit by a suffix scan.
 __global__ __launch_bounds__(1024) void k_select(uint64_t* __restrict__ surv, uint32_t* __restrict__ cnt,
                                                  float* __restrict__ thr, const float* __restrict__ invq,
-                                                 uint32_t* __restrict__ counters, int k1, float margin, int may_have_empty) {
+                                                 uint32_t* __restrict__ counters, int k1, float margin, int may_have_empty, int keep_max) {
     __shared__ uint32_t hist[16][256];
     __shared__ uint32_t tot[256];
     __shared__ uint64_t pivot_s;
@@ -132,7 +132,7 @@ __global__ __launch_bounds__(1024) void k_select(uint64_t* __restrict__ surv, ui
     for (int o = 32; o > 0; o >>= 1) mine += __shfl_xor(mine, o, 64);
     if (lane == 0 && mine) atomicAdd(&band_s, mine);
     __syncthreads();
-    if (band_s > (uint32_t)KEEP_MAX) cutkey = pivot;    // band too crowded: keep exactly the k1 best
+    if (band_s > (uint32_t)keep_max) cutkey = pivot;    // band too crowded: keep exactly the k1 best
 #pragma unroll
     for (int i = 0; i < 8; ++i)
         if (key[i] != 0 && key[i] >= cutkey) list[atomicAdd(&nout_s, 1u)] = key[i];
@@ -147,7 +147,7 @@ template <int DT>
 __global__ __launch_bounds__(1024) void k_rescore(const void* __restrict__ store_, const float* __restrict__ qf,
                                                   const double* __restrict__ invq64, const uint64_t* __restrict__ surv,
                                                   const uint32_t* __restrict__ cnt, double* __restrict__ exact,
-                                                  int nkb) {
+                                                  int nkb, int exact_stride) {
     // One workgroup per query; 16 lanes per candidate row, so a wavefront works on four rows at a
     // time and every lane has up to eight 16-byte loads in flight.
     const int b = blockIdx.x, sub = threadIdx.x & 15, grp = threadIdx.x >> 4;   // grp 0..63
@@ -197,7 +197,7 @@ __global__ __launch_bounds__(1024) void k_rescore(const void* __restrict__ store
         }
 #pragma unroll
         for (int o = 8; o > 0; o >>= 1) { dot += __shfl_xor(dot, o, 64); ssq += __shfl_xor(ssq, o, 64); }
-        if (live && sub == 0) exact[(int64_t)b * KEEP_MAX + j] = dot * invq64[b] * (1.0 / sqrt(ssq));
+        if (live && sub == 0) exact[(int64_t)b * exact_stride + j] = dot * invq64[b] * (1.0 / sqrt(ssq));
     }
 }
 
@@ -257,14 +257,14 @@ __global__ __launch_bounds__(RERANK_T) void k_rerank(const uint64_t* __restrict_
                                                 const double* __restrict__ exact, const float* __restrict__ qstage,
                                                 int k1, int k2, double lambda, int32_t* __restrict__ out_ids,
                                                 float* __restrict__ out_scores, int32_t* __restrict__ cand_ids,
-                                                float* __restrict__ cand_sims, EpsGreedy eg) {
+                                                float* __restrict__ cand_sims, EpsGreedy eg, int exact_stride) {
     __shared__ double v0[KEEP_MAX], v1[MEM_MAX_K1_INTERNAL];
     __shared__ int32_t i0[KEEP_MAX], i1[MEM_MAX_K1_INTERNAL];
     __shared__ double red[4];
     const int b = blockIdx.x, tid = threadIdx.x;
     const int kk = (int)cnt[b];
     for (int i = tid; i < kk; i += RERANK_T) {
-        v0[i] = exact[(int64_t)b * KEEP_MAX + i];
+        v0[i] = exact[(int64_t)b * exact_stride + i];
         i0[i] = key_id(surv[(int64_t)b * SURV_CAP + i]);
     }
     __syncthreads();

@@ -516,3 +516,39 @@ def test_masked_retrieval_matches_oracle(orc, dtype, N, d, nq):
     got = _check_masked(orc, bank, dtype, rows, q, few, allow2, np.full(nq, 0xffffffff, np.uint32), qtab, 0, k1, k2, 0.5)
     assert bank.counters() == (0, 0)
     bank.close()
+
+
+# ----------------------------------------------------------------------------- pools larger than 256 (Sec. 4.4, pool-size study)
+
+@pytest.mark.parametrize("dtype,N,d,nq,k1,k2", [
+    ("bf16", 40000, 128, 24, 960, 32),      # 30x over-retrieval
+    ("f16", 30000, 64, 9, 2048, 64),        # the largest pool
+    ("f32", 20000, 96, 3, 300, 300),        # VALU scan, k2 = k1: the whole pool comes back
+    ("bf16", 700, 64, 6, 1024, 16),         # pool larger than the bank
+])
+def test_large_pools_match_oracle(orc, dtype, N, d, nq, k1, k2):
+    rng = np.random.default_rng(N + k1)
+    rows, q = _unit(rng, N, d), _unit(rng, nq, d)
+    qtab = rng.uniform(-1, 1, (2, N)).astype(np.float32)
+    bank = _make_bank(dtype, rows, qtab, max_B=32, max_k1=2048)
+    st, qr = orc.round_to_store(rows, DT[dtype]), orc.round_to_store(q, DT[dtype])
+    for stage, lam in ((0, 0.5), (1, 1.0)):
+        gpu = parity.gpu_retrieve(bank, torch, q, stage, k1, k2, lam)
+        stats = parity.check_retrieve(orc, st, qr, qtab[stage], k1, k2, lam, gpu)
+        assert stats["queries"] == nq
+    # a small pool through the same handle still takes the small-pool kernels and matches
+    gpu = parity.gpu_retrieve(bank, torch, q, 0, 64, 8, 0.5)
+    parity.check_retrieve(orc, st, qr, qtab[0], 64, 8, 0.5, gpu)
+    # epsilon-greedy over the large pool
+    seed, step = 77, 12345
+    ids, sc, cid, _, ex = bank.retrieve_eps(_dev(q), 0, k1, k2, 0.5, 0.3, seed, step, want_candidates=True)
+    ids, sc, cid, ex = ids.cpu().numpy(), sc.cpu().numpy(), cid.cpu().numpy(), ex.cpu().numpy()
+    k1e = min(k1, N)
+    for b in range(nq):
+        pool = cid[b][:k1e]
+        w_ids, _, w_sc, w_ex = orc.rerank_eps(pool, orc.sims_of(st, qr[b], pool), qtab[0], 0.5, k2, 0.3, seed, step, b)
+        assert np.array_equal(ids[b], w_ids) and np.array_equal(ex[b], w_ex)
+        live = w_ids >= 0
+        assert np.all(np.abs(sc[b][live].astype(np.float64) - w_sc[live]) <= parity.TOL * np.maximum(1.0, np.abs(w_sc[live])))
+    assert bank.counters() == (0, 0)
+    bank.close()

@@ -38,7 +38,9 @@ def test_buffer_sizes(lib):
     w = lib.mem_workspace_bytes(1024, B.MEM_BF16, 1048576, 256, 128)
     assert w > 256 * 8192 * 8 and w % 256 == 0
     assert lib.mem_workspace_bytes(1024, B.MEM_BF16, 1048576, 0, 128) == 0
-    assert lib.mem_workspace_bytes(1024, B.MEM_BF16, 1048576, 256, 257) == 0
+    assert lib.mem_workspace_bytes(1024, B.MEM_BF16, 1048576, 256, 2049) == 0
+    big = lib.mem_workspace_bytes(1024, B.MEM_BF16, 1048576, 256, 2048)         # room for the larger selected lists
+    assert big - w == 256 * (2048 + 256 - 512) * 8
     assert lib.mem_workspace_bytes(1024, B.MEM_BF16, 1048576, 5000, 128) == 0
 
 
@@ -55,7 +57,7 @@ def test_argument_errors_without_gpu(lib):
     assert create(dt=7) == B.MEM_EINVAL and create(cap=0) == B.MEM_EINVAL
     assert create(store=None) == B.MEM_EINVAL and create(q=None) == B.MEM_EINVAL
     assert create(store=C.c_void_p(1000)) == B.MEM_EINVAL                      # misaligned
-    assert create(mb=0) == B.MEM_EINVAL and create(mk=300) == B.MEM_EINVAL and create(dev=-1) == B.MEM_EINVAL
+    assert create(mb=0) == B.MEM_EINVAL and create(mk=3000) == B.MEM_EINVAL and create(dev=-1) == B.MEM_EINVAL
     assert create(wbytes=wb - 1) == B.MEM_EWORKSPACE
     assert h.value is None
     # null handle everywhere
