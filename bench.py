@@ -215,7 +215,7 @@ def main():
     dense_rows = float(np.mean([r for _, r in dense]))
     alg_bytes = dense_rows * w.d * elem
     achieved = alg_bytes / (avg_ms * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": ("k_scan_gemv" if w.B <= 4 else "k_scan_mfma") + " (densest pass)", "achieved": round(achieved, 1),
+    roofline = {"bound": "hbm", "kernel": ("k_scan_gemv32" if w.B <= 4 and w.dtype == "f32" else "k_scan_mfma") + " (densest pass)", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None if args.batch else measured_traffic(args.workload),
                 "avg_launch_ms": round(avg_ms, 4), "launches": len(dense), "rows_per_launch": int(dense_rows),
                 "bytes_per_row": w.d * elem, "algorithmic_bytes_per_launch": int(alg_bytes),

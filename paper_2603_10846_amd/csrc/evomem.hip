@@ -26,7 +26,7 @@ static_assert(MEM_MAX_K1 == evk::BIG_K1_MAX, "header and kernels disagree on the
 namespace {
 
 constexpr int MAX_PROFILE = 4096;
-constexpr int GEMV_MAX_B = 4;       // at most this many queries use the VALU scan
+constexpr int GEMV_MAX_B = 4;       // fp32 stores: at most this many queries use the VALU scan
 
 inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
@@ -348,15 +348,8 @@ int launch_gemv(evomem* h, hipStream_t st, int B, const Level& L, const Mask& ma
     const float* qf = (const float*)(ws + h->w.qf);
     uint32_t* cnt = (uint32_t*)(ws + h->w.cnt);
     uint64_t* surv = (uint64_t*)(ws + h->w.surv);
-    if (h->dtype == MEM_F32)
-        hipLaunchKernelGGL(k_scan_gemv32<NB>, grid, block, 0, st, (const float*)h->store, (const float*)h->invnorm, qf, invq,
-                           thr, cnt, surv, h->N, h->nkb, B, L, mask);
-    else if (h->dtype == MEM_BF16)
-        hipLaunchKernelGGL((k_scan_gemv16<BF16, NB>), grid, block, 0, st, (const uint16_t*)h->store, (const float*)h->invnorm,
-                           qf, invq, thr, cnt, surv, h->N, h->nkb, B, L, mask);
-    else
-        hipLaunchKernelGGL((k_scan_gemv16<F16, NB>), grid, block, 0, st, (const uint16_t*)h->store, (const float*)h->invnorm,
-                           qf, invq, thr, cnt, surv, h->N, h->nkb, B, L, mask);
+    hipLaunchKernelGGL(k_scan_gemv32<NB>, grid, block, 0, st, (const float*)h->store, (const float*)h->invnorm, qf, invq,
+                       thr, cnt, surv, h->N, h->nkb, B, L, mask);
     LAUNCHCHK();
     return MEM_OK;
 }
@@ -381,7 +374,7 @@ static int retrieve_impl(evomem_t* h, const float* queries_dev, int B, int stage
     if (!queries_dev || !out_ids_dev || !out_scores_dev) return MEM_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     unsigned char* ws = h->ws;
-    const bool gemv = B <= GEMV_MAX_B;
+    const bool gemv = B <= GEMV_MAX_B && h->dtype == MEM_F32;
     // query tile of the MFMA scan and padded batch
     int qt = B <= 32 ? 32 : B <= 64 ? 64 : B <= 128 ? 128 : 256;
     const int Bp = gemv ? B : (int)round_up(B, qt);
