@@ -194,6 +194,16 @@ int mem_reward_stats(evomem_t* h, int stage, double* count, double* mean, double
 /* Forget the running statistics of a stage (asynchronous on the stream). */
 int mem_reward_stats_reset(evomem_t* h, int stage, void* hip_stream);
 
+/*
+ * Re-use of a bank across runs (Sec. 4.3 transfers a memory built on one set of tasks to others).
+ * Every buffer of a bank belongs to the caller, so saving a bank is copying the caller's store,
+ * inverse-norm, value-table (and tag) buffers together with mem_size().  To continue from such a
+ * copy: create a handle over buffers that already hold it (same d, dtype and capacity, so that the
+ * store layout is the same) and declare with mem_restore how many entries they hold.  Nothing is
+ * read or checked; n entries are simply taken to exist.  Errors: MEM_EINVAL (n < 0), MEM_ECAPACITY.
+ */
+int mem_restore(evomem_t* h, int64_t n);
+
 /* Copy stored rows first .. first+n, widened to fp32 and un-tiled, into dst_dev (float[n][d]). */
 int mem_read_rows(evomem_t* h, int64_t first, int64_t n, float* dst_dev, void* hip_stream);
 

@@ -43,6 +43,7 @@ SYMBOLS = {
                                     C.c_float, C.c_void_p, C.c_void_p]),
     "mem_reward_stats": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "mem_reward_stats_reset": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p]),
+    "mem_restore": (C.c_int, [C.c_void_p, C.c_int64]),
     "mem_update_q": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_void_p, C.c_float, C.c_void_p]),
     "mem_size": (C.c_int, [C.c_void_p, C.POINTER(C.c_int64)]),
     "mem_read_q": (C.c_int, [C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p]),
@@ -224,6 +225,26 @@ class MemoryBank:
 
     def reward_stats_reset(self, stage: int):
         _check(self.lib.mem_reward_stats_reset(self.h, stage, _stream()), "mem_reward_stats_reset")
+
+    def state(self) -> dict:
+        """Everything that makes up the bank, as host tensors (for saving)."""
+        out = {"d": self.d, "dtype": self.dtype, "capacity": self.capacity, "size": self.size(),
+               "store": self.store.cpu(), "invnorm": self.invnorm.cpu(), "q": self.q.cpu()}
+        if self._tags is not None:
+            out["tags"] = self._tags.cpu()
+        return out
+
+    def load_state(self, st: dict):
+        """Continue from a bank saved with state() (same d, dtype and capacity)."""
+        assert (st["d"], st["dtype"], st["capacity"]) == (self.d, self.dtype, self.capacity)
+        self.store.copy_(st["store"])
+        self.invnorm.copy_(st["invnorm"])
+        self.q.copy_(st["q"])
+        if "tags" in st:
+            self.set_tags(0, torch.zeros(0, dtype=torch.int64))       # attaches the tag buffer
+            self._tags.copy_(st["tags"])
+        torch.cuda.synchronize(self.device)
+        _check(self.lib.mem_restore(self.h, st["size"]), "mem_restore")
 
     def read_q(self, stage: int, first: int = 0, n: int | None = None) -> torch.Tensor:
         n = self.size() - first if n is None else n

@@ -243,6 +243,13 @@ int mem_reward_stats_reset(evomem_t* h, int stage, void* hip_stream) {
     return MEM_OK;
 }
 
+int mem_restore(evomem_t* h, int64_t n) {
+    if (!h || n < 0) return MEM_EINVAL;
+    if (n > h->capacity) return MEM_ECAPACITY;
+    h->N = n;
+    return MEM_OK;
+}
+
 const char* mem_strerror(int s) {
     switch (s) {
         case MEM_OK: return "ok";

@@ -552,3 +552,34 @@ def test_large_pools_match_oracle(orc, dtype, N, d, nq, k1, k2):
         assert np.all(np.abs(sc[b][live].astype(np.float64) - w_sc[live]) <= parity.TOL * np.maximum(1.0, np.abs(w_sc[live])))
     assert bank.counters() == (0, 0)
     bank.close()
+
+
+# ----------------------------------------------------------------------------- a bank saved and continued
+
+def test_bank_saved_and_restored_gives_identical_results(orc):
+    rng = np.random.default_rng(109)
+    N, d = 6000, 80
+    rows, q = _unit(rng, N, d), _unit(rng, 12, d)
+    qtab = rng.uniform(-1, 1, (2, N)).astype(np.float32)
+    a = _make_bank("bf16", rows, qtab, capacity=8000, max_B=16, max_k1=64)
+    a.set_tags(0, torch.from_numpy((rng.integers(0, 3, N) | (rng.integers(0, 5, N) << 8)).astype(np.int64)))
+    a.update_q(_dev(rng.integers(0, N, 500).astype(np.int32)), 1, _dev(rng.random(500).astype(np.float32)), 0.2)
+    saved = a.state()
+    want = parity.gpu_retrieve(a, torch, q, 1, 64, 8, 0.5)
+    al, ex = torch.full((12,), 0b101, dtype=torch.int64), torch.full((12,), 2, dtype=torch.int64)
+    want_m = [t.cpu().numpy() for t in a.retrieve_masked(_dev(q), 1, 64, 8, 0.5, al, ex)[:2]]
+    a.close()
+    b = B.MemoryBank(d, "bf16", 8000, max_B=16, max_k1=64)
+    assert b.size() == 0
+    b.load_state(saved)
+    assert b.size() == N
+    got = parity.gpu_retrieve(b, torch, q, 1, 64, 8, 0.5)
+    for k in want:
+        assert np.array_equal(want[k].view(np.uint32), got[k].view(np.uint32)), k
+    got_m = [t.cpu().numpy() for t in b.retrieve_masked(_dev(q), 1, 64, 8, 0.5, al, ex)[:2]]
+    assert np.array_equal(want_m[0], got_m[0]) and np.array_equal(want_m[1].view(np.uint32), got_m[1].view(np.uint32))
+    # and it keeps growing from where it was
+    assert b.append(_dev(_unit(rng, 10, d))) == N
+    with pytest.raises(B.MemError):
+        b.lib and B._check(b.lib.mem_restore(b.h, 9000), "mem_restore")
+    b.close()
