@@ -451,11 +451,11 @@ static int retrieve_impl(evomem_t* h, const float* queries_dev, int B, int stage
             hipLaunchKernelGGL(k_rescore<2>, rgrid, dim3(1024), 0, st, (const void*)h->store, (const float*)qf, (const double*)invq64, (const uint64_t*)surv, (const uint32_t*)cnt, exact, h->nkb, exact_stride);
         LAUNCHCHK();
     }
-    if (k1 <= MEM_MAX_K1_INTERNAL) {
+    if (k1 <= 128) {                       // counting ranks is quadratic: measured faster than sorting up to here
         hipLaunchKernelGGL(k_rerank, dim3(B), dim3(RERANK_T), 0, st, (const uint64_t*)surv, (const uint32_t*)cnt, (const double*)exact,
                            (const float*)(h->q + (int64_t)stage * h->capacity), k1, k2, (double)lambda, out_ids_dev, out_scores_dev,
                            out_cand_ids_dev, out_cand_sims_dev, eg, exact_stride);
-    } else {                               // large pools: sorts instead of counting ranks
+    } else {                               // larger pools: sorts instead of counting ranks
         int cap = 2;
         while (cap < keep_of(k1)) cap <<= 1;
         const size_t lds = rerank_big_lds(cap, k1, k2);
