@@ -155,7 +155,8 @@ __global__ __launch_bounds__(1024) void k_rescore(const void* __restrict__ store
     const float* q = qf + (int64_t)b * nkb * KB;
     constexpr int EPC = DT == 0 ? 4 : 8;                 // elements per 16-byte chunk
     const int nch = nkb * KB / EPC;                      // chunks per row
-    for (int j0 = 0; j0 < n; j0 += 64) {                 // uniform trip count: the shuffles below need all lanes
+    // (gridDim.y workgroups share a query: workgroup y takes the candidate groups y, y + gridDim.y, ...)
+    for (int j0 = 64 * (int)blockIdx.y; j0 < n; j0 += 64 * (int)gridDim.y) {   // uniform trip count: the shuffles below need all lanes
         const int j = j0 + grp;
         const bool live = j < n;
         const int32_t id = live ? key_id(surv[(int64_t)b * SURV_CAP + j]) : 0;
