@@ -1,21 +1,27 @@
-// Similarity scan for query batches large enough to be a dense contraction (Sec. 3.2, dense
-// recall): scores[q][n] = <query q, bank row n> on the matrix cores, never written to memory.
+// Similarity scan on the matrix cores (Sec. 3.2, dense recall): scores[q][n] = <query q, bank row n>,
+// never written to memory.  Used for every batch size on 16-bit stores (at a handful of queries the
+// arithmetic is idle and the kernel is a streaming engine for the bank) and for more than four
+// queries on fp32 stores.
 //
-// Persistent workgroups of 4 wavefronts; each owns QT queries and walks over 256-row bank tiles.
-// Per k-block the bank tile's 32 KB block (already in LDS operand order in HBM, see layout.h) and
-// the queries' block are staged in LDS (two stages) and consumed by v_mfma_f32_32x32x16 (bf16 or
-// f16 operands, fp32 accumulation).  Global loads run two k-blocks ahead of the MFMAs through two
-// register sets, and the (tile, k-block) sequence is flattened, so the loads of the next tile are
-// already in flight while a tile's epilogue runs.  Queries are the rows of the accumulator tile and
-// bank rows its columns: a lane holds one bank row per 32x32 block and the row's inverse norm is a
-// per-lane constant in the epilogue.
+// Persistent workgroups of 4 or 8 wavefronts; each owns QT queries and walks over 256-row bank
+// tiles.  Per k-block the bank tile's 32 KB block (already in LDS operand order in HBM, see
+// layout.h) and the queries' block are staged in LDS (two stages) and consumed by
+// v_mfma_f32_32x32x16 (bf16 or f16 operands, fp32 accumulation).  Global loads run two k-blocks
+// ahead of the MFMAs through two register sets, and the (tile, k-block) sequence is flattened, so
+// the loads of the next tile are already in flight while a tile's epilogue runs.  Queries are the
+// rows of the accumulator tile and bank rows its columns: a lane holds one bank row per 32x32 block.
+// Within a k-block the four k-steps are a hand-written software pipeline (see compute()): operand
+// fragments are read from LDS one k-step ahead, the LDS stores and global loads of the following
+// k-blocks issue between the MFMAs, and there is one workgroup barrier per k-block.
 //
 // fp32 stores: each value is split on the fly into bf16 hi + bf16 lo and the product is
 // hi*hi + hi*lo + lo*hi (three MFMAs, relative error of a product about 2^-16); this only has to
 // be good enough for the filter, since the value filter re-scores the selected candidates in fp64.
 //
-// Epilogue: score * invnorm[row] is compared with the query's threshold (pre-divided by the
-// query's inverse norm); the rare survivors are appended to the query's list.
+// Filter: the accumulators of a tile start at  -threshold[query] * norm[row]  (one extra MFMA per
+// block), so after the k-loop a score passes iff its accumulator is non-negative; the epilogue
+// collects sign bits, stages the rare survivors in an LDS list and flushes it every few tiles.
+// The sparsest pass has no threshold and writes every row's key to the row's own position.
 #pragma once
 #include <type_traits>
 
