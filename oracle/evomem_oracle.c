@@ -306,6 +306,53 @@ int orc_rerank_eps(const int32_t* cand_ids, const double* cand_sims, int count,
     return 0;
 }
 
+/* ---------- start-point selection (Sec. 3.4) ---------- */
+
+/* One start point out of a task's set P(x), by the refining stage's values (or any stage's table):
+ * the member with the largest Q, the lower id among equals (a NaN value counts as -inf); with
+ * probability eps instead a uniformly random position of the set (epsilon-greedy, the policy
+ * Sec. 4.4 states for start points as for contexts).  ids: the set in the caller's order, n of them;
+ * ids outside [0, N) are not members (their number is returned).  The draw is Philox-4x32-10 with
+ * key = seed and counter = (step low, step high, set_index, 0xffffffff): word 0 decides (explore iff
+ * word0 < floor(eps * 2^32)), word 1 picks position floor(word1 * members / 2^32) among the members
+ * in array order.  An empty set gives id -1, value 0, explored 0. */
+int64_t orc_select_by_q(const int32_t* ids, int64_t n, const float* qtable, int64_t N, float eps,
+                        uint64_t seed, uint64_t step, uint32_t set_index,
+                        int32_t* out_id, float* out_q, unsigned char* explored) {
+    int64_t members = 0, skipped = 0;
+    int32_t best = -1;
+    double best_q = 0.0;
+    for (int64_t i = 0; i < n; ++i) {
+        int32_t id = ids[i];
+        if (id < 0 || id >= N) { ++skipped; continue; }
+        double q = (double)qtable[id];
+        if (q != q) q = -INFINITY;
+        if (members == 0 || q > best_q || (q == best_q && id < best)) { best = id; best_q = q; }
+        ++members;
+    }
+    *out_id = -1; *out_q = 0.0f;
+    if (explored) *explored = 0;
+    if (members == 0) return skipped;
+    const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    const uint32_t ctr[4] = {(uint32_t)step, (uint32_t)(step >> 32), set_index, 0xffffffffu};
+    uint32_t rnd[4];
+    orc_philox4x32_10(ctr, key, rnd);
+    const uint64_t thr = (uint64_t)((double)eps * 4294967296.0);
+    if ((uint64_t)rnd[0] < thr) {
+        int64_t want = (int64_t)(((uint64_t)rnd[1] * (uint64_t)members) >> 32), seen = 0;
+        for (int64_t i = 0; i < n; ++i) {
+            int32_t id = ids[i];
+            if (id < 0 || id >= N) continue;
+            if (seen == want) { best = id; break; }
+            ++seen;
+        }
+        if (explored) *explored = 1;
+    }
+    *out_id = best;
+    *out_q = qtable[best];
+    return skipped;
+}
+
 /* ---------- step 3: unified value update ---------- */
 
 /* Reference: fp64 state seeded from the fp32 table, rounded back to fp32 once at the end.

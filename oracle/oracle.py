@@ -54,6 +54,9 @@ def _load():
         L.orc_recall_masked.restype = C.c_int
         L.orc_shape_rewards.argtypes = [C.c_int, u8p, f32p, f32p, C.c_int64, C.c_int, C.c_double, C.c_double, f64p, f32p]
         L.orc_shape_rewards.restype = C.c_int
+        L.orc_select_by_q.argtypes = [i32p, C.c_int64, f32p, C.c_int64, C.c_float, C.c_uint64, C.c_uint64, C.c_uint32,
+                                      i32p, f32p, u8p]
+        L.orc_select_by_q.restype = C.c_int64
         L.orc_update_q64.argtypes = [f32p, C.c_int64, i32p, f32p, C.c_int64, C.c_double]
         L.orc_update_q64.restype = C.c_int64
         L.orc_update_q32.argtypes = [f32p, C.c_int64, i32p, f32p, C.c_int64, C.c_float]
@@ -200,6 +203,25 @@ def shape_rewards(stage: int, feasible, latency, best_latency, normalise: bool, 
     if rc:
         raise RuntimeError("orc_shape_rewards failed")
     return out, st
+
+
+def select_by_q(set_ids, set_offsets, qtable, eps: float = 0.0, seed: int = 0, step: int = 0):
+    """Start-point selection (Sec. 3.4) for G sets given as one id array and G + 1 offsets into it.
+    Returns (ids int32[G], values f32[G], explored u8[G], number of ids that are no members)."""
+    set_ids = np.ascontiguousarray(set_ids, np.int32)
+    off = np.ascontiguousarray(set_offsets, np.int64)
+    qtable = _f32(qtable)
+    G = off.size - 1
+    out_id, out_q, ex = np.empty(G, np.int32), np.empty(G, np.float32), np.empty(G, np.uint8)
+    skipped = 0
+    for g in range(G):
+        part = np.ascontiguousarray(set_ids[off[g]:off[g + 1]])
+        one_id, one_q, one_ex = np.empty(1, np.int32), np.empty(1, np.float32), np.empty(1, np.uint8)
+        skipped += _load().orc_select_by_q(_p(part, C.c_int32), part.size, _p(qtable, C.c_float), qtable.size,
+                                           float(np.float32(eps)), seed, step, g,
+                                           _p(one_id, C.c_int32), _p(one_q, C.c_float), _p(one_ex, C.c_ubyte))
+        out_id[g], out_q[g], ex[g] = one_id[0], one_q[0], one_ex[0]
+    return out_id, out_q, ex, int(skipped)
 
 
 def update_q64(qtable, ids, rewards, alpha: float):

@@ -75,6 +75,8 @@ def load():
     global _lib
     if _lib is None:
         if not os.path.exists(LIB_PATH):
+            if os.environ.get("EVOMEM_LIB"):
+                raise FileNotFoundError(f"EVOMEM_LIB names {LIB_PATH}, which does not exist")
             build_library()
         lib = C.CDLL(LIB_PATH)
         for name, (res, args) in SYMBOLS.items():

@@ -456,6 +456,103 @@ def test_eps_planted_mistakes_are_caught(orc):
     assert differs_all and differs_word
 
 
+# ----------------------------------------------------------------------------- start-point selection (Sec. 3.4)
+
+def _sets(rng, n_table, G, max_len=40, bad=True):
+    parts, off = [], [0]
+    for g in range(G):
+        n = int(rng.integers(0, max_len + 1))
+        ids = rng.integers(0, n_table, n).astype(np.int32)              # repeats allowed
+        if bad and n:
+            ids[rng.random(n) < 0.1] = rng.choice([-1, -7, n_table, n_table + 5])
+        parts.append(ids); off.append(off[-1] + n)
+    return (np.concatenate(parts) if parts else np.zeros(0, np.int32)), np.array(off, np.int64)
+
+
+def test_start_point_greedy_against_python_definition(orc):
+    """eps = 0: the member with the largest value, the lower id among equals; invalid ids are no members."""
+    rng = np.random.default_rng(21)
+    for trial in range(20):
+        n_table = int(rng.integers(1, 60))
+        q = rng.choice([-1.0, -0.25, 0.0, 0.5, 1.0], n_table).astype(np.float32)   # many ties
+        ids, off = _sets(rng, n_table, 12)
+        got_id, got_q, ex, skipped = orc.select_by_q(ids, off, q)
+        want_skipped = 0
+        for g in range(12):
+            members = [int(i) for i in ids[off[g]:off[g + 1]] if 0 <= i < n_table]
+            want_skipped += int(off[g + 1] - off[g]) - len(members)
+            if not members:
+                assert got_id[g] == -1 and got_q[g] == 0.0
+                continue
+            best = max(float(q[i]) for i in members)
+            assert got_id[g] == min(i for i in members if float(q[i]) == best)
+            assert got_q[g] == q[got_id[g]]
+        assert skipped == want_skipped and not ex.any()
+
+
+def test_start_point_special_cases(orc):
+    q = np.array([0.25, 0.25, 0.25, 0.25], np.float32)
+    assert orc.select_by_q([3, 1, 2], [0, 3], q)[0][0] == 1                       # all equal: the lowest id
+    assert orc.select_by_q([2], [0, 1], q)[0][0] == 2                             # a set of one
+    assert orc.select_by_q([2], [0, 1], q, eps=1.0, seed=9, step=4)[0][0] == 2    # ... also when exploring
+    q2 = np.array([np.nan, -np.inf, -3.0, -0.0, 0.0], np.float32)
+    assert orc.select_by_q([0, 1], [0, 2], q2)[0][0] == 0                         # NaN counts as -inf: tie, lower id
+    assert orc.select_by_q([0, 1, 2], [0, 3], q2)[0][0] == 2
+    assert orc.select_by_q([4, 3], [0, 2], q2)[0][0] == 3                         # -0 == +0: tie, lower id
+    out = orc.select_by_q([-1, 9], [0, 2], q2)
+    assert out[0][0] == -1 and out[1][0] == 0.0 and out[3] == 2                   # no member at all
+
+
+def test_start_point_exploration_draws(orc):
+    """eps = 1 always explores and takes position floor(word1 * members / 2^32) among the members in array
+    order, words from the Python Philox with counter (step, set index, 0xffffffff); the stream differs from the
+    one the context slots use (last counter word = slot index)."""
+    rng = np.random.default_rng(22)
+    n_table = 300
+    q = rng.uniform(-1, 1, n_table).astype(np.float32)
+    ids, off = _sets(rng, n_table, 30, max_len=25)
+    seed, step = 0x1234567890abcdef, (7 << 32) | 11
+    got_id, got_q, ex, _ = orc.select_by_q(ids, off, q, eps=1.0, seed=seed, step=step)
+    same_as_slot0 = 0
+    for g in range(30):
+        members = [int(i) for i in ids[off[g]:off[g + 1]] if 0 <= i < n_table]
+        if not members:
+            assert got_id[g] == -1 and ex[g] == 0
+            continue
+        r = _philox_py([step & 0xffffffff, step >> 32, g, 0xffffffff], [seed & 0xffffffff, seed >> 32])
+        assert ex[g] == 1 and got_id[g] == members[(r[1] * len(members)) >> 32] and got_q[g] == q[got_id[g]]
+        r0 = _philox_py([step & 0xffffffff, step >> 32, g, 0], [seed & 0xffffffff, seed >> 32])
+        same_as_slot0 += r0[:2] == r[:2]
+    assert same_as_slot0 == 0
+    # rate of exploration and uniformity over positions, one set of 16 distinct members, 4000 steps
+    members = rng.permutation(n_table)[:16].astype(np.int32)
+    hits, explored = np.zeros(16, int), 0
+    for t in range(4000):
+        i, _, e, _ = orc.select_by_q(members, [0, 16], q, eps=1.0, seed=5, step=t)
+        hits[list(members).index(int(i[0]))] += 1
+        explored += int(orc.select_by_q(members, [0, 16], q, eps=0.25, seed=6, step=t)[2][0])
+    assert hits.min() > 250 - 6 * 15.3 and hits.max() < 250 + 6 * 15.3           # binomial(4000, 1/16): sigma 15.3
+    assert abs(explored / 4000 - 0.25) < 5 * math.sqrt(0.25 * 0.75 / 4000)
+
+
+def test_start_point_planted_mistakes_are_caught(orc):
+    """Plausible wrong readings give other answers on these inputs: ties to the higher id, the first maximum in
+    array order, positions counted over invalid ids too."""
+    q = np.array([0.5, 0.9, 0.9, 0.1, 0.9], np.float32)
+    ids = np.array([4, 2, 1, 3], np.int32)
+    got = int(orc.select_by_q(ids, [0, 4], q)[0][0])
+    assert got == 1 and got != 4 and got != max(1, 2, 4)                           # first-in-array would say 4
+    ids2 = np.array([-1, 3, -1, 0, 2], np.int32)
+    differs = False
+    for t in range(50):
+        r = _philox_py([t, 0, 0, 0xffffffff], [1, 0])
+        got = int(orc.select_by_q(ids2, [0, 5], q, eps=1.0, seed=1, step=t)[0][0])
+        assert got == [3, 0, 2][(r[1] * 3) >> 32]
+        wrong = int(ids2[(r[1] * 5) >> 32])                                       # counting the invalid ones
+        differs |= wrong != got
+    assert differs
+
+
 # ----------------------------------------------------------------------------- stage rewards and their normalisation
 
 def test_stage_rewards_closed_forms(orc):
