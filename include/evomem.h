@@ -195,6 +195,29 @@ int mem_reward_stats(evomem_t* h, int stage, double* count, double* mean, double
 int mem_reward_stats_reset(evomem_t* h, int stage, void* hip_stream);
 
 /*
+ * Start-point selection (Sec. 3.4: among the start points P(x) available for a task, one is
+ * selected using Q_2; Sec. 4.4: by the same epsilon-greedy policy as the contexts).  G sets at once:
+ * set g is set_ids_dev[set_offsets_dev[g] .. set_offsets_dev[g+1]) (int32 ids, int64 offsets, G + 1
+ * of them, non-decreasing, within [0, n_ids]; offsets outside that range are clamped to it).  Ids
+ * outside [0, size) are not members of their set; they are counted in mem_counters' skipped ids.
+ *   out_ids_dev       int32[G]  the member with the largest value in the stage's table, the lower id
+ *                     among equal values (-0 equals +0, a NaN value counts as -inf); -1 for a set
+ *                     without members
+ *   out_q_dev         float[G]  that entry's value as stored; 0 for a set without members
+ *   out_explored_dev  uint8[G]  1 where the random branch chose; may be NULL
+ * With probability eps a set takes, instead of its best member, the member at a uniformly random
+ * position (a repeated id is as many times more likely).  The draw is Philox-4x32 with 10 rounds,
+ * key = seed, counter = (step low, step high, g, 0xffffffff) -- the last word keeps it apart from
+ * the draws of mem_retrieve_eps' slots under the same seed and step.  Word 0 decides (explore iff
+ * word0 < floor(eps * 2^32)), word 1 picks position floor(word1 * members / 2^32) in array order.
+ * G = 0 is a no-op.  Errors: MEM_EINVAL (null pointers, G < 0, n_ids < 0, stage, eps outside [0,1]
+ * or NaN), MEM_EHIP.
+ */
+int mem_select_by_q(evomem_t* h, const int32_t* set_ids_dev, int64_t n_ids, const int64_t* set_offsets_dev,
+                    int G, int stage, float eps, uint64_t seed, uint64_t step, int32_t* out_ids_dev,
+                    float* out_q_dev, unsigned char* out_explored_dev, void* hip_stream);
+
+/*
  * Re-use of a bank across runs (Sec. 4.3 transfers a memory built on one set of tasks to others).
  * Every buffer of a bank belongs to the caller, so saving a bank is copying the caller's store,
  * inverse-norm, value-table (and tag) buffers together with mem_size().  To continue from such a
@@ -207,7 +230,8 @@ int mem_restore(evomem_t* h, int64_t n);
 /* Copy stored rows first .. first+n, widened to fp32 and un-tiled, into dst_dev (float[n][d]). */
 int mem_read_rows(evomem_t* h, int64_t first, int64_t n, float* dst_dev, void* hip_stream);
 
-/* Synchronises the device.  *skipped_ids: ids mem_update_q skipped so far; *overflows: queries
+/* Synchronises the device.  *skipped_ids: ids outside the bank that mem_update_q and mem_select_by_q
+ * have skipped so far; *overflows: queries
  * whose survivor list overflowed during some retrieve (their pool may then be inexact). */
 int mem_counters(evomem_t* h, int64_t* skipped_ids, int64_t* overflows);
 

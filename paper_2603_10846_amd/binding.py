@@ -45,6 +45,8 @@ SYMBOLS = {
     "mem_reward_stats_reset": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p]),
     "mem_restore": (C.c_int, [C.c_void_p, C.c_int64]),
     "mem_update_q": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_void_p, C.c_float, C.c_void_p]),
+    "mem_select_by_q": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int, C.c_int, C.c_float, C.c_uint64,
+                                  C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "mem_size": (C.c_int, [C.c_void_p, C.POINTER(C.c_int64)]),
     "mem_read_q": (C.c_int, [C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p]),
     "mem_read_rows": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p]),
@@ -186,6 +188,20 @@ class MemoryBank:
         assert ids.is_contiguous() and rewards.is_contiguous() and ids.numel() == rewards.numel()
         _check(self.lib.mem_update_q(self.h, _ptr(ids), ids.numel(), stage, _ptr(rewards), alpha, _stream()),
                "mem_update_q")
+
+    def select_by_q(self, set_ids: torch.Tensor, set_offsets: torch.Tensor, stage: int, eps: float = 0.0,
+                    seed: int = 0, step: int = 0):
+        """Start point of each of G sets (ids int32 concatenated, offsets int64[G + 1]) by the stage's values,
+        epsilon-greedy.  Returns (ids int32[G], values f32[G], explored u8[G])."""
+        assert set_ids.is_cuda and set_ids.dtype == torch.int32 and set_ids.is_contiguous()
+        assert set_offsets.is_cuda and set_offsets.dtype == torch.int64 and set_offsets.is_contiguous()
+        G = set_offsets.numel() - 1
+        ids = torch.empty(max(G, 0), dtype=torch.int32, device=self.device)
+        vals = torch.empty(max(G, 0), dtype=torch.float32, device=self.device)
+        explored = torch.empty(max(G, 0), dtype=torch.uint8, device=self.device)
+        _check(self.lib.mem_select_by_q(self.h, _ptr(set_ids), set_ids.numel(), _ptr(set_offsets), G, stage, eps, seed,
+                                        step, _ptr(ids), _ptr(vals), _ptr(explored), _stream()), "mem_select_by_q")
+        return ids, vals, explored
 
     def set_tags(self, first: int, tags: torch.Tensor):
         """Tags of entries first..: an integer tensor of values < 2^32 (type = tag & 0xff, group = tag >> 8)."""

@@ -16,6 +16,7 @@
 #include "k_select.h"
 #include "k_rerank_big.h"
 #include "k_reward.h"
+#include "k_startpoint.h"
 #include "k_update.h"
 #include "layout.h"
 
@@ -523,6 +524,20 @@ extern "C" int mem_retrieve_masked(evomem_t* h, const float* queries_dev, int B,
     const EpsGreedy greedy{0, 0, 0, nullptr};
     return retrieve_impl(h, queries_dev, B, stage, k1, k2, lambda, out_ids_dev, out_scores_dev, out_cand_ids_dev,
                          out_cand_sims_dev, hip_stream, greedy, Mask{h->tags, allow_types_dev, exclude_group_dev});
+}
+
+extern "C" int mem_select_by_q(evomem_t* h, const int32_t* set_ids_dev, int64_t n_ids, const int64_t* set_offsets_dev,
+                               int G, int stage, float eps, uint64_t seed, uint64_t step, int32_t* out_ids_dev,
+                               float* out_q_dev, unsigned char* out_explored_dev, void* hip_stream) {
+    if (!h || G < 0 || n_ids < 0 || (stage != 0 && stage != 1) || !(eps >= 0.f && eps <= 1.f)) return MEM_EINVAL;
+    if (G == 0) return MEM_OK;
+    if (!set_offsets_dev || !out_ids_dev || !out_q_dev || (n_ids > 0 && !set_ids_dev)) return MEM_EINVAL;
+    const EpsGreedy eg{(uint64_t)((double)eps * 4294967296.0), seed, step, out_explored_dev};
+    hipLaunchKernelGGL(k_select_by_q, dim3((unsigned)G), dim3(SP_LANES), 0, static_cast<hipStream_t>(hip_stream),
+                       set_ids_dev, n_ids, set_offsets_dev, (const float*)(h->q + (int64_t)stage * h->capacity), h->N, eg,
+                       out_ids_dev, out_q_dev, (uint32_t*)(h->ws + h->w.counters));
+    LAUNCHCHK();
+    return MEM_OK;
 }
 
 extern "C" int mem_update_q(evomem_t* h, const int32_t* ids_dev, int64_t M, int stage, const float* rewards_dev,

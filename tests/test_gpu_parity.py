@@ -583,3 +583,74 @@ def test_bank_saved_and_restored_gives_identical_results(orc):
     with pytest.raises(B.MemError):
         b.lib and B._check(b.lib.mem_restore(b.h, 9000), "mem_restore")
     b.close()
+
+
+# ----------------------------------------------------------------------------- start-point selection (Sec. 3.4)
+
+def _start_sets(rng, N, G, lens):
+    parts, off = [], [0]
+    for g in range(G):
+        n = int(lens[g % len(lens)])
+        ids = rng.integers(0, N, n).astype(np.int32)
+        if n:
+            ids[rng.random(n) < 0.05] = rng.choice([-1, N, N + 3, 2**31 - 1, -2**31])
+        parts.append(ids); off.append(off[-1] + n)
+    return np.concatenate(parts), np.array(off, np.int64)
+
+
+@pytest.mark.parametrize("eps", [0.0, 0.3, 1.0])
+def test_select_by_q_matches_oracle(orc, eps):
+    """Ids, values and exploration flags bit-exact: empty sets, singletons, sets spanning several chunks of the
+    workgroup, repeated ids, ids outside the bank, tied values (the table has few distinct values, +-0, NaN, -inf)."""
+    rng = np.random.default_rng(300)
+    N = 20000
+    qtab = np.zeros((2, N), np.float32)
+    qtab[0] = rng.uniform(-1, 1, N)
+    qtab[1] = rng.choice(np.array([-np.inf, -1.0, -0.0, 0.0, 0.5, np.nan], np.float32), N)
+    bank = _make_bank("bf16", _unit(rng, N, 64), qtab, max_B=8, max_k1=16)
+    lens = [0, 1, 2, 7, 63, 64, 65, 255, 256, 257, 1000, 1024, 1025, 5000, 0, 33]
+    ids, off = _start_sets(rng, N, 64, lens)
+    skipped_total = 0
+    for stage, seed, step in ((0, 11, 0), (1, 2**63 + 5, (9 << 32) | 77)):
+        got_id, got_q, got_ex = bank.select_by_q(_dev(ids), _dev(off), stage, eps, seed, step)
+        want_id, want_q, want_ex, skipped = orc.select_by_q(ids, off, qtab[stage], eps, seed, step)
+        skipped_total += skipped
+        assert np.array_equal(got_id.cpu().numpy(), want_id)
+        assert np.array_equal(got_q.cpu().numpy().view(np.uint32), want_q.view(np.uint32))
+        assert np.array_equal(got_ex.cpu().numpy(), want_ex)
+        if eps == 0.0:
+            assert not want_ex.any()
+        if eps == 1.0:
+            assert want_ex[want_id >= 0].all()
+    assert bank.counters() == (skipped_total, 0) and skipped_total > 0
+    bank.close()
+
+
+def test_select_by_q_follows_updates_and_rejects_bad_arguments(orc):
+    """The selection reads the table mem_update_q writes; argument errors are reported, not executed."""
+    rng = np.random.default_rng(301)
+    N = 3000
+    bank = _make_bank("f16", _unit(rng, N, 32), max_B=8, max_k1=16)
+    ids = np.array([5, 9, 12, 700, 2999], np.int32)
+    off = np.array([0, 5], np.int64)
+    got, val, _ = bank.select_by_q(_dev(ids), _dev(off), 1)
+    assert int(got[0]) == 5 and float(val[0]) == 0.0                       # all values 0: the lowest id
+    bank.update_q(_dev(np.array([700, 12, 700], np.int32)), 1, _dev(np.array([1.0, 0.2, 1.0], np.float32)), 0.5)
+    table, _ = orc.update_q32(np.zeros(N, np.float32), np.array([700, 12, 700], np.int32),
+                              np.array([1.0, 0.2, 1.0], np.float32), 0.5)
+    got, val, _ = bank.select_by_q(_dev(ids), _dev(off), 1)
+    assert int(got[0]) == 700 and float(val[0]) == table[700]
+    got, _, _ = bank.select_by_q(_dev(ids), _dev(off), 0)                  # the other stage's table is untouched
+    assert int(got[0]) == 5
+    # offsets that point outside the id array are clamped to it
+    got, _, _ = bank.select_by_q(_dev(ids), _dev(np.array([-4, 3, 99], np.int64)), 1)
+    assert got.cpu().tolist() == [12, 700]
+    empty = bank.select_by_q(_dev(ids), _dev(np.array([0], np.int64)), 1)
+    assert empty[0].numel() == 0
+    for kwargs in ({"stage": 2}, {"eps": 1.5}, {"eps": float("nan")}, {"eps": -0.1}):
+        args = {"stage": 1, "eps": 0.0}
+        args.update(kwargs)
+        with pytest.raises(B.MemError) as e:
+            bank.select_by_q(_dev(ids), _dev(off), args["stage"], args["eps"])
+        assert e.value.status == B.MEM_EINVAL
+    bank.close()
