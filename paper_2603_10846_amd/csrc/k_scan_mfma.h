@@ -45,10 +45,21 @@ __device__ __forceinline__ f32x16_t mfma32(u32x4_t a, u32x4_t b, f32x16_t c) {
     }
 }
 
+// Two fp32 values rounded to bf16 (round to nearest even) and packed, a first: one v_cvt_pk_bf16_f32.
+__device__ __forceinline__ uint32_t cvt_pk_bf16(float a, float b) {
+    typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+    const f32x2_t v = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+
+// hi/lo split of two fp32 values for the matrix cores: returns the packed bf16 heads and leaves the
+// (exactly representable) remainders a - head(a), b - head(b) in ra, rb.
 __device__ __forceinline__ uint32_t pack_bf16x2_hi(float a, float b, float& ra, float& rb) {
-    uint16_t ha = f2bf16_rne(a), hb = f2bf16_rne(b);
-    ra = a - bf16_to_f(ha); rb = b - bf16_to_f(hb);
-    return ha | ((uint32_t)hb << 16);
+    const uint32_t h = cvt_pk_bf16(a, b);
+    ra = a - __uint_as_float(h << 16);
+    rb = b - __uint_as_float(h & 0xffff0000u);
+    return h;
 }
 
 // Per-lane choice between two registers by a lane mask (one v_cndmask).  Written as an instruction
@@ -235,8 +246,8 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
                 float r0, r1, r2, r3;
                 u32x2_t hi, lo;
                 hi.x = pack_bf16x2_hi(f0, f1, r0, r1); hi.y = pack_bf16x2_hi(f2, f3, r2, r3);
-                lo.x = f2bf16_rne(r0) | ((uint32_t)f2bf16_rne(r1) << 16);
-                lo.y = f2bf16_rne(r2) | ((uint32_t)f2bf16_rne(r3) << 16);
+                lo.x = cvt_pk_bf16(r0, r1);
+                lo.y = cvt_pk_bf16(r2, r3);
                 unsigned char* rowp = sbank(s) + r * 128 + (c4 & 1) * 8;
                 *reinterpret_cast<u32x2_t*>(rowp + swz16(c4 >> 1, r) * 16) = hi;
                 *reinterpret_cast<u32x2_t*>(rowp + swz16(4 + (c4 >> 1), r) * 16) = lo;
