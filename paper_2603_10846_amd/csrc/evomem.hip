@@ -335,7 +335,11 @@ template <int DT, bool MASKED>
 int launch_mfma_dt(evomem* h, hipStream_t st, int Bp, int qt, const Level& L, int k1, const Mask& mask, int B) {
     switch (qt) {
         case 32: return launch_mfma<DT, 1, 1, 2, 4, MASKED>(h, st, Bp, L, k1, mask, B);
-        case 64: return launch_mfma<DT, 2, 1, 2, 4, MASKED>(h, st, Bp, L, k1, mask, B);
+        case 64:
+            // fp32 stores: 8 wavefronts, so that one wavefront's hi/lo split (vector ALU) overlaps the
+            // MFMAs of the other one on its SIMD (measured 0.054 -> 0.047 ms on the 65,536 x 1024 bank)
+            if constexpr (DT == 0) return launch_mfma<DT, 1, 2, 2, 4, MASKED>(h, st, Bp, L, k1, mask, B);
+            else return launch_mfma<DT, 2, 1, 2, 4, MASKED>(h, st, Bp, L, k1, mask, B);
         case 128: return launch_mfma<DT, 2, 2, 2, 4, MASKED>(h, st, Bp, L, k1, mask, B);   // 8 wavefronts, 64 x 64 each
         default: return launch_mfma<DT, 4, 2, 2, 4, MASKED>(h, st, Bp, L, k1, mask, B);    // 8 wavefronts, 128 x 64 each
     }
