@@ -354,14 +354,19 @@ int launch_mfma_any(evomem* h, hipStream_t st, int Bp, int qt, const Level& L, i
 template <int NB>
 int launch_gemv(evomem* h, hipStream_t st, int B, const Level& L, const Mask& mask) {
     unsigned char* ws = h->ws;
-    dim3 grid((unsigned)L.ntiles), block(256);
+    const bool split = L.ntiles < 1024;        // few tiles: four workgroups per tile
+    dim3 grid((unsigned)(split ? 4 * L.ntiles : L.ntiles)), block(256);
     const float* invq = (const float*)(ws + h->w.invq);
     const float* thr = (const float*)(ws + h->w.thr);
     const float* qf = (const float*)(ws + h->w.qf);
     uint32_t* cnt = (uint32_t*)(ws + h->w.cnt);
     uint64_t* surv = (uint64_t*)(ws + h->w.surv);
-    hipLaunchKernelGGL(k_scan_gemv32<NB>, grid, block, 0, st, (const float*)h->store, (const float*)h->invnorm, qf, invq,
-                       thr, cnt, surv, h->N, h->nkb, B, L, mask);
+    if (split)
+        hipLaunchKernelGGL((k_scan_gemv32<NB, 4>), grid, block, 0, st, (const float*)h->store, (const float*)h->invnorm, qf, invq,
+                           thr, cnt, surv, h->N, h->nkb, B, L, mask);
+    else
+        hipLaunchKernelGGL((k_scan_gemv32<NB, 16>), grid, block, 0, st, (const float*)h->store, (const float*)h->invnorm, qf, invq,
+                           thr, cnt, surv, h->N, h->nkb, B, L, mask);
     LAUNCHCHK();
     return MEM_OK;
 }

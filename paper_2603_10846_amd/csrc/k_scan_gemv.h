@@ -15,6 +15,8 @@
 // k-block, and 16 such loads cover the tile; the partial sums of a row are combined with
 // cross-lane adds at the end.  A similarity that reaches the query's current threshold (the k1-th
 // best found by sparser passes, minus a rounding margin) is appended to the query's survivor list.
+// A pass with few tiles (a small bank) gives each tile to four workgroups of 64 rows each, so that
+// more compute units pull on the memory system: such a pass is bound by latency, not bandwidth.
 #pragma once
 #include "layout.h"
 
@@ -27,7 +29,8 @@ __device__ __forceinline__ void append_survivor(float v, float invq_b, int32_t i
 }
 
 // fp32 stores: CH = 16 chunks of 4 elements per 256-byte segment.
-template <int NB>
+// RG: groups of 16 rows a workgroup scans (16 = a whole tile; 4 = a quarter, gridDim.x = 4 * tiles).
+template <int NB, int RG>
 __global__ __launch_bounds__(256) void k_scan_gemv32(const float* __restrict__ store,
                                                      const float* __restrict__ invnorm,
                                                      const float* __restrict__ qf, const float* __restrict__ invq,
@@ -35,24 +38,26 @@ __global__ __launch_bounds__(256) void k_scan_gemv32(const float* __restrict__ s
                                                      uint64_t* __restrict__ surv, int64_t N, int nkb, int B,
                                                      Level L, Mask mask) {
     const int tid = threadIdx.x, c = tid & 15, rbase = tid >> 4;   // rbase 0..15
-    const int64_t t = level_tile(L, blockIdx.x);
+    constexpr int PARTS = 16 / RG;
+    const int tile_j = (int)blockIdx.x / PARTS, g0 = ((int)blockIdx.x % PARTS) * RG;   // first row group
+    const int64_t t = level_tile(L, tile_j);
     const int dpad = nkb * KB;
-    float acc[16][NB];
+    float acc[RG][NB];
 #pragma unroll
-    for (int i = 0; i < 16; ++i)
+    for (int i = 0; i < RG; ++i)
 #pragma unroll
         for (int b = 0; b < NB; ++b) acc[i][b] = 0.f;
-    const float* blk = store + t * nkb * (int64_t)BLOCK_ELEMS + rbase * KB + c * 4;
+    const float* blk = store + t * nkb * (int64_t)BLOCK_ELEMS + (g0 * 16 + rbase) * KB + c * 4;
     for (int kb = 0; kb < nkb; ++kb, blk += BLOCK_ELEMS) {
-        float4 x[16];
+        float4 x[RG];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) x[i] = *reinterpret_cast<const float4*>(blk + i * 16 * KB);
+        for (int i = 0; i < RG; ++i) x[i] = *reinterpret_cast<const float4*>(blk + i * 16 * KB);
         float4 qv[NB];
 #pragma unroll
         for (int b = 0; b < NB; ++b)
             qv[b] = *reinterpret_cast<const float4*>(qf + (int64_t)(b < B ? b : 0) * dpad + kb * KB + c * 4);
 #pragma unroll
-        for (int i = 0; i < 16; ++i)
+        for (int i = 0; i < RG; ++i)
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
                 float a = acc[i][b];
@@ -62,7 +67,7 @@ __global__ __launch_bounds__(256) void k_scan_gemv32(const float* __restrict__ s
             }
     }
 #pragma unroll
-    for (int i = 0; i < 16; ++i)
+    for (int i = 0; i < RG; ++i)
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
             float v = acc[i][b];
@@ -70,9 +75,9 @@ __global__ __launch_bounds__(256) void k_scan_gemv32(const float* __restrict__ s
             acc[i][b] = v;
         }
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
+    for (int i = 0; i < RG; ++i) {
         if (c != i) continue;
-        int64_t id = t * TILE_ROWS + i * 16 + rbase;
+        int64_t id = t * TILE_ROWS + (g0 + i) * 16 + rbase;
         if (id >= N) continue;
         float inve = invnorm[id];
         const uint32_t tag = mask.tags ? mask.tags[id] : 0u;
@@ -82,7 +87,7 @@ __global__ __launch_bounds__(256) void k_scan_gemv32(const float* __restrict__ s
             float v = acc[i][b] * inve;
             const bool ok = !mask.tags || eligible(tag, mask.allow[b], mask.exclude[b]);
             if (L.rho == 0)      // sparsest pass keeps every row at its own position, no counter (0 = empty slot)
-                surv[(int64_t)b * SURV_CAP + (int64_t)blockIdx.x * TILE_ROWS + (id - t * TILE_ROWS)] = ok ? pack_key(v * invq[b], (int32_t)id) : 0ull;
+                surv[(int64_t)b * SURV_CAP + (int64_t)tile_j * TILE_ROWS + (id - t * TILE_ROWS)] = ok ? pack_key(v * invq[b], (int32_t)id) : 0ull;
             else if (ok && v >= thr[b]) append_survivor(v, invq[b], (int32_t)id, cnt + b, surv + (int64_t)b * SURV_CAP);
         }
     }
