@@ -133,6 +133,29 @@ def test_edge_cases(orc):
     bank.close()
 
 
+@pytest.mark.parametrize("dtype,N,d,nq,k1,k2", [
+    ("f16", 1500, 16384, 2, 16, 4),      # largest dimension (256 k-blocks), MFMA scan
+    ("f32", 1200, 16384, 1, 16, 4),      # largest dimension, fp32 VALU scan
+    ("bf16", 1000, 8, 3, 8, 2),          # smallest dimension (padded to one k-block)
+    ("bf16", 5000, 64, 4096, 32, 4),     # largest batch: sixteen 256-query tiles
+    ("f32", 3000, 72, 4095, 16, 4),      # largest batch but one, fp32 rows through the bf16 split
+])
+def test_maximum_sizes(orc, dtype, N, d, nq, k1, k2):
+    rng = np.random.default_rng(N + d + nq)
+    rows = _unit(rng, N, d)
+    q = _unit(rng, nq, d)
+    qtab = rng.uniform(-1, 1, (2, N)).astype(np.float32)
+    bank = _make_bank(dtype, rows, qtab, max_B=nq, max_k1=k1)
+    gpu = parity.gpu_retrieve(bank, torch, q, 1, k1, k2, 0.5)
+    st, qr = orc.round_to_store(rows, DT[dtype]), orc.round_to_store(q, DT[dtype])
+    sample = None if nq <= 8 else sorted(set([0, 1, 255, 256, 257, 1000, 2047, 2048, 3000, nq - 2, nq - 1]))
+    parity.check_retrieve(orc, st, qr, qtab[1], k1, k2, 0.5, gpu, sample=sample)
+    assert np.all(gpu["cand_ids"] >= 0) and np.all(np.diff(gpu["cand_sims"], axis=1) <= 0)
+    assert np.all(np.diff(gpu["scores"], axis=1) <= 0)
+    assert bank.counters() == (0, 0)
+    bank.close()
+
+
 def test_survivor_list_overflow_is_counted(orc):
     """More rows tie with the pool's last member than a survivor list holds (8192): the query is counted by
     mem_counters, the call still returns a valid pool of exact ties, and later calls are unaffected."""
