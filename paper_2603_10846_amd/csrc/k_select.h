@@ -29,6 +29,18 @@ __device__ __forceinline__ void bitonic_desc(T* a, int n, int tid, int nthreads,
     __syncthreads();
 }
 
+// OR over the 64 lanes of a wavefront (all lanes active); lane 63 ends up with the result.
+__device__ __forceinline__ uint32_t wave_or_u32(uint32_t x) {
+    int v = (int)x;
+    v |= __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);   // row_shr:1
+    v |= __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);   // row_shr:2
+    v |= __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);   // row_shr:4
+    v |= __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true);   // row_shr:8
+    v |= __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, true);   // row_bcast:15 into rows 1 and 3
+    v |= __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, true);   // row_bcast:31 into rows 2 and 3
+    return (uint32_t)v;
+}
+
 // After a scan pass, for one query: find the k1-th best survivor key (similarity desc, id asc) by
 // an MSB-first radix select over the packed 64-bit keys, set the next pass's threshold to that
 // similarity minus `margin` (a bound on the scan's fp32 rounding error, so that no true member of
@@ -36,14 +48,15 @@ __device__ __forceinline__ void bitonic_desc(T* a, int n, int tid, int nthreads,
 // before applying it), and compact every key whose similarity reaches that threshold to the head of
 // the list: these seed the next pass and, after the last pass, are the candidates that get re-scored
 // in fp64.  Nothing is sorted here -- slot order is irrelevant to every consumer.
-// Keys live in registers (8 per lane, 1024 lanes); each radix pass builds per-wavefront digit
-// histograms in LDS, sums them, and one wavefront picks the digit by a suffix scan.
+// Keys live in registers (8 per lane, 1024 lanes); the passes start at the highest bit on which two
+// keys differ; each builds per-wavefront digit histograms in LDS, sums them, and one wavefront
+// picks the digit by a suffix scan.
 __global__ __launch_bounds__(1024) void k_select(uint64_t* __restrict__ surv, uint32_t* __restrict__ cnt,
                                                  float* __restrict__ thr, const float* __restrict__ invq,
                                                  uint32_t* __restrict__ counters, int k1, float margin, int may_have_empty, int keep_max) {
     __shared__ uint32_t hist[16][256];
     __shared__ uint32_t tot[256];
-    __shared__ uint64_t pivot_s;
+    __shared__ uint64_t pivot_s, or_s[16];
     __shared__ uint32_t sel_digit, sel_need, sel_single, band_s, nout_s;
     const int b = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     uint64_t* list = surv + (int64_t)b * SURV_CAP;
@@ -57,6 +70,7 @@ __global__ __launch_bounds__(1024) void k_select(uint64_t* __restrict__ surv, ui
     uint64_t key[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) { int idx = i * 1024 + tid; key[i] = idx < n ? list[idx] : 0ull; }   // 0 = empty
+    const uint64_t ref = n > 0 ? list[0] : 0ull;      // any one key (or an empty slot), see the radix passes
     if (tid == 0) { band_s = 0; nout_s = 0; }
     if (may_have_empty) {               // uniform
         // A masked sparsest pass leaves the slots of rows the query does not accept empty (key 0): if
@@ -81,22 +95,37 @@ __global__ __launch_bounds__(1024) void k_select(uint64_t* __restrict__ surv, ui
         if (tid == 0) band_s = 0;
         __syncthreads();
     }
-    uint64_t prefix = 0, pivot = 0;
+    // Bits that all keys share need no pass: the survivors of a filtering pass lie in a narrow band
+    // of similarities, so the leading 12-20 bits of their keys are the same, and a pass over such
+    // bits would also send every key to one histogram bin (same-address LDS atomics serialise).
+    // (the bits on which some key differs from the list's first key, OR-ed over the workgroup)
+    uint64_t differ = 0ull;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+        if (key[i] != 0) differ |= key[i] ^ ref;
+    differ = ((uint64_t)wave_or_u32((uint32_t)(differ >> 32)) << 32) | wave_or_u32((uint32_t)differ);
+    if (lane == 63) or_s[wave] = differ;
+    for (int i = tid; i < 16 * 256; i += 1024) (&hist[0][0])[i] = 0;
+    __syncthreads();
+    differ = 0ull;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) differ |= or_s[w];               // 0 only if there is a single key
+    int hi = differ ? 63 - __builtin_clzll(differ) : 7;           // highest bit on which two keys differ
+    uint64_t prefix = hi < 63 ? (ref >> (hi + 1)) << (hi + 1) : 0ull, pivot = 0;
     uint32_t need = (uint32_t)k1;
-    for (int pass = 0; pass < 8; ++pass) {
-        const int shift = 56 - 8 * pass;
-        for (int i = tid; i < 16 * 256; i += 1024) (&hist[0][0])[i] = 0;
-        __syncthreads();
+    for (;;) {
+        const int shift = hi >= 7 ? hi - 7 : 0;               // this pass ranks bits hi .. shift
+        const uint32_t dmask = (1u << (hi - shift + 1)) - 1u;
 #pragma unroll
         for (int i = 0; i < 8; ++i)
-            if (key[i] != 0 && (pass == 0 || (key[i] >> (shift + 8)) == (prefix >> (shift + 8))))
-                atomicAdd(&hist[wave][(uint32_t)(key[i] >> shift) & 255u], 1u);
+            if (key[i] != 0 && (hi == 63 || (key[i] >> (hi + 1)) == (prefix >> (hi + 1))))
+                atomicAdd(&hist[wave][(uint32_t)(key[i] >> shift) & dmask], 1u);
         __syncthreads();
         if (tid < 256) {
-            uint32_t s = 0;
+            uint32_t sum = 0;
 #pragma unroll
-            for (int w = 0; w < 16; ++w) s += hist[w][tid];
-            tot[tid] = s;
+            for (int w = 0; w < 16; ++w) { sum += hist[w][tid]; hist[w][tid] = 0; }   // cleared for the next pass
+            tot[tid] = sum;
         }
         __syncthreads();
         if (wave == 0) {                // lane l owns digits 4l .. 4l+3; larger digit = better key
@@ -114,7 +143,7 @@ __global__ __launch_bounds__(1024) void k_select(uint64_t* __restrict__ surv, ui
         __syncthreads();
         prefix |= (uint64_t)sel_digit << shift;
         need = sel_need;
-        if (sel_single || pass == 7) {              // one key left under this prefix: it is the k1-th best
+        if (sel_single || shift == 0) {             // one key left under this prefix: it is the k1-th best
 #pragma unroll
             for (int i = 0; i < 8; ++i)
                 if (key[i] != 0 && (key[i] >> shift) == (prefix >> shift)) pivot_s = key[i];
@@ -122,6 +151,7 @@ __global__ __launch_bounds__(1024) void k_select(uint64_t* __restrict__ surv, ui
             pivot = pivot_s;
             break;
         }
+        hi = shift - 1;
     }
     const float tau = key_sim(pivot) - margin;
     uint64_t cutkey = (uint64_t)f2ord(tau) << 32;   // every key with similarity >= tau compares >= cutkey
