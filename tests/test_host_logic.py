@@ -75,6 +75,28 @@ def test_argument_errors_without_gpu(lib):
     assert lib.mem_strerror(99) == b"unknown status"
 
 
+def test_null_handle_on_the_later_entry_points(lib):
+    fake = C.c_void_p(256 * 1000)
+    assert lib.mem_retrieve_eps(None, fake, 1, 0, 4, 2, 0.5, 0.1, 1, 2, fake, fake, None, None, None, None) == B.MEM_EINVAL
+    assert lib.mem_retrieve_masked(None, fake, 1, 0, 4, 2, 0.5, fake, fake, fake, fake, None, None, None) == B.MEM_EINVAL
+    assert lib.mem_select_by_q(None, fake, 4, fake, 1, 1, 0.0, 0, 0, fake, fake, None, None) == B.MEM_EINVAL
+    assert lib.mem_attach_tags(None, fake) == B.MEM_EINVAL
+    assert lib.mem_set_tags(None, 0, 1, fake, None) == B.MEM_EINVAL
+    assert lib.mem_restore(None, 0) == B.MEM_EINVAL
+
+
+def test_a_missing_library_named_by_the_environment_is_an_error():
+    """EVOMEM_LIB selects another build of the library; a path that does not exist must not be
+    papered over by building or loading something else."""
+    import subprocess
+    import sys
+    code = ("import os, sys; sys.path.insert(0, %r); os.environ['EVOMEM_LIB'] = '/nonexistent/libevomem.so';\n"
+            "from paper_2603_10846_amd import binding\n"
+            "try:\n    binding.load()\nexcept FileNotFoundError as e:\n    print('refused')\n" % ROOT)
+    out = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=120)
+    assert out.stdout.strip() == "refused", out.stderr[-500:]
+
+
 @pytest.mark.parametrize("N,k1", [(1, 1), (255, 4), (4096, 32), (8192, 256), (8193, 256), (65536, 64),
                                   (1000003, 128), (1048576, 128), (4194304, 128), (8388608, 256),
                                   (3000000, 7), (2**31 - 257, 256)])
