@@ -156,6 +156,55 @@ def test_maximum_sizes(orc, dtype, N, d, nq, k1, k2):
     bank.close()
 
 
+def _random_case(i):
+    rng = np.random.default_rng(7000 + i)
+    dtype = ["f32", "bf16", "f16"][int(rng.integers(0, 3))]
+    N = int(rng.choice([1, 2, 31, 255, 256, 257, 1000, 5000, 8191, 8193, 20000, 40000]))
+    d = int(rng.choice([8, 16, 56, 64, 72, 128, 200, 256, 512]))
+    nq = int(rng.choice([1, 2, 4, 5, 31, 32, 33, 64, 65, 128, 129, 257, 300]))
+    k1 = int(rng.choice([1, 2, 7, 16, 33, 64, 128, 129, 200, 256]))
+    k2 = int(rng.integers(1, k1 + 1))
+    lam = float(rng.choice([0.0, 1.0, rng.uniform(0, 1)]))
+    return dtype, N, d, nq, k1, k2, lam, int(rng.integers(0, 2))
+
+
+@pytest.mark.parametrize("i", range(60))
+def test_random_configurations(orc, i):
+    """Seeded random shapes around the kernels' tile and dispatch boundaries (row tiles of 256, query tiles of
+    32 / 64 / 128 / 256, the 4-query switch of fp32 stores, the 128-entry switch of the value filter, one or
+    several passes), duplicated rows for exact ties, every query or 16 sampled ones against the oracle."""
+    dtype, N, d, nq, k1, k2, lam, stage = _random_case(i)
+    rng = np.random.default_rng(9000 + i)
+    rows = _unit(rng, N, d)
+    if N >= 31:
+        rows[rng.integers(0, N, 8)] = rows[int(rng.integers(0, N))]       # exact ties on similarity
+    q = _unit(rng, nq, d)
+    qtab = rng.uniform(-1, 1, (2, N)).astype(np.float32)
+    bank = _make_bank(dtype, rows, qtab, max_B=nq, max_k1=k1)
+    gpu = parity.gpu_retrieve(bank, torch, q, stage, k1, k2, lam)
+    st, qr = orc.round_to_store(rows, DT[dtype]), orc.round_to_store(q, DT[dtype])
+    sample = None if nq <= 16 else sorted(set(rng.integers(0, nq, 14).tolist() + [0, nq - 1]))
+    parity.check_retrieve(orc, st, qr, qtab[stage], k1, k2, lam, gpu, sample=sample)
+    # the same call with epsilon-greedy slot filling, wherever the greedy order of the pool is not a near-tie
+    eps, seed, step = float(rng.choice([0.1, 0.5, 1.0])), int(rng.integers(0, 2**63)), int(rng.integers(0, 2**40))
+    ids, sc, cid, _, ex = bank.retrieve_eps(_dev(q), stage, k1, k2, lam, eps, seed, step, want_candidates=True)
+    torch.cuda.synchronize()
+    ids, cid, ex = ids.cpu().numpy(), cid.cpu().numpy(), ex.cpu().numpy()
+    assert np.array_equal(cid, gpu["cand_ids"])
+    k1e = min(k1, N)
+    for b in (range(nq) if sample is None else sample):
+        pool = cid[b][:k1e]
+        sims = orc.sims_of(st, qr[b], pool)
+        _, _, order_sc = orc.rerank(pool, sims, qtab[stage], lam, k1e)
+        gaps = -np.diff(order_sc)
+        if np.any((gaps > 0) & (gaps < 1e-7)):                    # (exact ties are ordered by id on both sides)
+            continue
+        w_ids, _, _, w_ex = orc.rerank_eps(pool, sims, qtab[stage], lam, k2, eps, seed, step, b)
+        assert np.array_equal(ids[b], w_ids) and np.array_equal(ex[b], w_ex), f"query {b}"
+    assert bank.counters() == (0, 0)
+    bank.close()
+
+
 def test_survivor_list_overflow_is_counted(orc):
     """More rows tie with the pool's last member than a survivor list holds (8192): the query is counted by
     mem_counters, the call still returns a valid pool of exact ties, and later calls are unaffected."""
