@@ -27,8 +27,10 @@
  *   - Value filter: score = (1-lambda) z(sim) + lambda z(Q_stage), z being the z-score over the
  *     query's own candidate pool (population standard deviation, denominator std + 1e-6).
  *     lambda = 0 ranks by similarity alone, lambda = 1 by the stage's Q alone.
- *   - All functions return a mem_status; nothing throws or aborts.  NaN or zero-norm inputs give
- *     unspecified results (not checked on the hot path).
+ *   - All functions return a mem_status; nothing throws or aborts.  NaN, infinite or zero-norm rows,
+ *     queries and Q values are not checked on the hot path: which items such a call returns is
+ *     unspecified, but it is well formed (every id is -1 or an entry of the bank, none twice in a
+ *     pool) and later calls are unaffected.
  */
 #ifndef EVOMEM_H
 #define EVOMEM_H

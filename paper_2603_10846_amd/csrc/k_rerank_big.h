@@ -54,7 +54,7 @@ __global__ __launch_bounds__(BIG_T) void k_rerank_big(const uint64_t* __restrict
     const int kk = (int)cnt[b];
     for (int i = tid; i < cap; i += BIG_T) {
         const bool live = i < kk;
-        val[i] = live ? exact[(int64_t)b * exact_stride + i] : -INFINITY;     // padding sorts last
+        val[i] = live ? finite_or_lowest(exact[(int64_t)b * exact_stride + i]) : -INFINITY;     // padding sorts last (its id is the largest)
         kid[i] = live ? key_id(surv[(int64_t)b * SURV_CAP + i]) : 0x7fffffff;
         idx[i] = (uint32_t)i;
     }
@@ -102,7 +102,7 @@ __global__ __launch_bounds__(BIG_T) void k_rerank_big(const uint64_t* __restrict
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             const int i = tid + u * BIG_T;
-            if (i < k1e) sco[i] = (1.0 - lambda) * (d_s[u] * scale_s) + lambda * (d_q[u] * scale_q);
+            if (i < k1e) sco[i] = finite_or_lowest((1.0 - lambda) * (d_s[u] * scale_s) + lambda * (d_q[u] * scale_q));
         }
     }
     // ordering 2: pool positions by (score desc, id asc); the index array is reused (pool padded to a power of two)

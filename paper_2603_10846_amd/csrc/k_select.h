@@ -273,6 +273,11 @@ __device__ __forceinline__ double block_sum(double* red, int tid, double x) {
     return r;
 }
 
+// A NaN similarity or score (a zero-norm or non-finite row or query, a NaN in the Q table: inputs
+// for which the results are unspecified) is ranked as -inf, so that the orderings below stay total
+// orders: every rank is taken exactly once and every id that is gathered with is a real one.
+__device__ __forceinline__ double finite_or_lowest(double v) { return v == v ? v : -INFINITY; }
+
 // (v, id) before (w, jd)?  Written without short-circuit operators: inside the counting loops below
 // the arguments come from LDS, and a short-circuit form compiles to a branch per element with the
 // second LDS read behind it, so that every element pays two LDS round trips (measured: 200 cycles
@@ -299,7 +304,7 @@ __global__ __launch_bounds__(RERANK_T) void k_rerank(const uint64_t* __restrict_
     const int b = blockIdx.x, tid = threadIdx.x;
     const int kk = (int)cnt[b];
     for (int i = tid; i < kk; i += RERANK_T) {
-        v0[i] = exact[(int64_t)b * exact_stride + i];
+        v0[i] = finite_or_lowest(exact[(int64_t)b * exact_stride + i]);
         i0[i] = key_id(surv[(int64_t)b * SURV_CAP + i]);
     }
     __syncthreads();
@@ -332,7 +337,7 @@ __global__ __launch_bounds__(RERANK_T) void k_rerank(const uint64_t* __restrict_
         const double var_s = block_sum(red, tid, ds * ds) / k1e;
         const double var_q = block_sum(red, tid, dq * dq) / k1e;
         const double scale_s = 1.0 / (sqrt(var_s) + 1e-6), scale_q = 1.0 / (sqrt(var_q) + 1e-6);
-        if (mine) score = (1.0 - lambda) * (ds * scale_s) + lambda * (dq * scale_q);
+        if (mine) score = finite_or_lowest((1.0 - lambda) * (ds * scale_s) + lambda * (dq * scale_q));
     }
     __syncthreads();
     // ordering 2: the k2 best by (score desc, id asc); v0/i0 are reused for the scores

@@ -205,6 +205,49 @@ def test_random_configurations(orc, i):
     bank.close()
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+def test_degenerate_rows_and_queries_give_well_formed_results(orc, dtype):
+    """A zero row, a row with a NaN, a row with an infinity, a zero query and a NaN query: the results
+    for them are unspecified, but every call returns, every id is -1 or a real entry, no id repeats within
+    a pool, and the entry points that follow are unaffected."""
+    rng = np.random.default_rng(555)
+    N, d = (20000 if dtype == "bf16" else 3000), 64            # the larger bank takes two passes (a NaN threshold)
+    rows = _unit(rng, N, d)
+    rows[5] = 0.0
+    rows[17, 3] = np.nan
+    rows[40, 0] = np.inf
+    q = _unit(rng, 8, d)
+    q[6] = 0.0
+    q[7, 1] = np.nan
+    qtab = rng.uniform(-1, 1, (2, N)).astype(np.float32)
+    qtab[1, 100] = np.nan                                                # a poisoned value too
+    bank = _make_bank(dtype, rows, qtab, max_B=8, max_k1=300)
+    for nq in (3, 8):
+        for k1, k2, stage in ((16, 4, 0), (200, 8, 1), (300, 300, 1)):
+            out = parity.gpu_retrieve(bank, torch, q[:nq], stage, k1, k2, 0.5)
+            for name in ("ids", "cand_ids"):
+                a = out[name]
+                assert a.min() >= -1 and a.max() < N, (name, nq, k1)
+                for b in range(nq):
+                    live = a[b][a[b] >= 0]
+                    assert live.size == np.unique(live).size, (name, nq, k1, b)
+            ids, _, _, _, ex = bank.retrieve_eps(_dev(q[:nq]), stage, k1, k2, 0.5, 0.5, 3, 4)
+            ids = ids.cpu().numpy()
+            assert ids.min() >= -1 and ids.max() < N
+    ids = out["ids"].reshape(-1).astype(np.int32)
+    bank.update_q(_dev(ids), 1, _dev(np.ones(ids.size, np.float32)), 0.1)
+    got, _, _ = bank.select_by_q(_dev(np.arange(N, dtype=np.int32)), _dev(np.array([0, N], np.int64)), 1)
+    assert 0 <= int(got[0]) < N
+    bank.close()
+    # a clean bank right afterwards behaves as usual
+    clean = _unit(rng, 2000, d)
+    bank = _make_bank(dtype, clean, max_B=8, max_k1=32)
+    gpu = parity.gpu_retrieve(bank, torch, q[:6], 0, 32, 4, 0.5)
+    parity.check_retrieve(orc, orc.round_to_store(clean, DT[dtype]), orc.round_to_store(q[:6], DT[dtype]),
+                          np.zeros(2000, np.float32), 32, 4, 0.5, gpu)
+    bank.close()
+
+
 def test_survivor_list_overflow_is_counted(orc):
     """More rows tie with the pool's last member than a survivor list holds (8192): the query is counted by
     mem_counters, the call still returns a valid pool of exact ties, and later calls are unaffected."""
