@@ -180,7 +180,7 @@ def test_random_configurations(orc, i):
         rows[rng.integers(0, N, 8)] = rows[int(rng.integers(0, N))]       # exact ties on similarity
     q = _unit(rng, nq, d)
     qtab = rng.uniform(-1, 1, (2, N)).astype(np.float32)
-    bank = _make_bank(dtype, rows, qtab, max_B=nq, max_k1=k1)
+    bank = _make_bank(dtype, rows, qtab, max_B=nq, max_k1=k1, chunk=int(rng.choice([97, 256, 1000, 65536])))   # ragged appends
     gpu = parity.gpu_retrieve(bank, torch, q, stage, k1, k2, lam)
     st, qr = orc.round_to_store(rows, DT[dtype]), orc.round_to_store(q, DT[dtype])
     sample = None if nq <= 16 else sorted(set(rng.integers(0, nq, 14).tolist() + [0, nq - 1]))
@@ -246,6 +246,34 @@ def test_degenerate_rows_and_queries_give_well_formed_results(orc, dtype):
     parity.check_retrieve(orc, orc.round_to_store(clean, DT[dtype]), orc.round_to_store(q[:6], DT[dtype]),
                           np.zeros(2000, np.float32), 32, 4, 0.5, gpu)
     bank.close()
+
+
+def test_calls_on_a_side_stream_and_two_banks_at_once(orc):
+    """The stream is an argument of every call: work issued on a non-default stream gives the same results,
+    and two banks alive on one device do not disturb each other."""
+    rng = np.random.default_rng(77)
+    rows_a, rows_b = _unit(rng, 9000, 128), _unit(rng, 5000, 64)
+    qa, qb = _unit(rng, 40, 128), _unit(rng, 3, 64)
+    bank_a = _make_bank("bf16", rows_a, max_B=64, max_k1=32)
+    bank_b = _make_bank("f32", rows_b, max_B=8, max_k1=32)
+    ref_a = parity.gpu_retrieve(bank_a, torch, qa, 0, 32, 4, 0.5)
+    ref_b = parity.gpu_retrieve(bank_b, torch, qb, 0, 16, 4, 0.5)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        got_b = bank_b.retrieve(_dev(qb), 0, 16, 4, 0.5, want_candidates=True)
+        got_a = bank_a.retrieve(_dev(qa), 0, 32, 4, 0.5, want_candidates=True)
+        ids = got_a[0].reshape(-1).contiguous()
+        bank_a.update_q(ids, 0, torch.ones(ids.numel(), device="cuda:0"), 0.25)
+    side.synchronize()
+    assert np.array_equal(got_a[0].cpu().numpy(), ref_a["ids"]) and np.array_equal(got_a[2].cpu().numpy(), ref_a["cand_ids"])
+    assert np.array_equal(got_b[0].cpu().numpy(), ref_b["ids"]) and np.array_equal(got_b[1].cpu().numpy(), ref_b["scores"])
+    want, _ = orc.update_q32(np.zeros(9000, np.float32), ref_a["ids"].reshape(-1).astype(np.int32),
+                             np.ones(ref_a["ids"].size, np.float32), 0.25)
+    assert np.array_equal(bank_a.read_q(0).cpu().numpy().view(np.uint32), want.view(np.uint32))
+    assert np.all(bank_b.read_q(0).cpu().numpy() == 0)
+    bank_a.close()
+    bank_b.close()
 
 
 def test_survivor_list_overflow_is_counted(orc):
