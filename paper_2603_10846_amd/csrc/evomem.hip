@@ -429,6 +429,10 @@ static int retrieve_impl(evomem_t* h, const float* queries_dev, int B, int stage
     if (!gemv) eps += 2e-5f;                             // threshold * norm carried as 16-bit hi/lo pairs
     const float margin = 2.f * eps;
 
+    // Pools of up to 128 with one workgroup per query in the gather (more than 128 queries): the last
+    // selection, the re-scoring and the value filter run as one launch (measured on the 1M x 1024 bank at
+    // 256 queries: see the kernel).
+    const bool fused_tail = h->N > 0 && k1 <= 128 && B > 128;
     if (h->N > 0) {
         for (const Level& L : levels) {
             const bool prof = h->prof_on && h->prof_n < MAX_PROFILE;
@@ -449,8 +453,21 @@ static int retrieve_impl(evomem_t* h, const float* queries_dev, int B, int stage
                 int64_t rows = (int64_t)L.ntiles * TILE_ROWS;
                 h->prof_rows[h->prof_n++] = rows;
             }
+            if (fused_tail && &L == &levels.back()) break;          // the last selection runs inside the fused kernel below
             hipLaunchKernelGGL(k_select, dim3(B), dim3(1024), 0, st, surv, cnt, thr, (const float*)invq, counters, k1, margin, mask.tags != nullptr, keep_of(k1));
             LAUNCHCHK();
+        }
+        if (fused_tail) {
+            const float* qs = (const float*)(h->q + (int64_t)stage * h->capacity);
+#define EVK_TAIL(DT) hipLaunchKernelGGL(k_select_rescore_rerank<DT>, dim3(B), dim3(1024), 0, st, surv, cnt, thr, (const float*)invq, counters, \
+                k1, margin, mask.tags != nullptr, keep_of(k1), (const void*)h->store, (const float*)qf, (const double*)invq64, exact, h->nkb,      \
+                exact_stride, qs, k2, (double)lambda, out_ids_dev, out_scores_dev, out_cand_ids_dev, out_cand_sims_dev, eg)
+            if (h->dtype == MEM_F32) EVK_TAIL(0);
+            else if (h->dtype == MEM_BF16) EVK_TAIL(1);
+            else EVK_TAIL(2);
+#undef EVK_TAIL
+            LAUNCHCHK();
+            return MEM_OK;
         }
         // a query's candidates are split over several workgroups when there are few queries, so that the
         // gather occupies the whole device

@@ -51,14 +51,14 @@ __device__ __forceinline__ uint32_t wave_or_u32(uint32_t x) {
 // Keys live in registers (8 per lane, 1024 lanes); the passes start at the highest bit on which two
 // keys differ; each builds per-wavefront digit histograms in LDS, sums them, and one wavefront
 // picks the digit by a suffix scan.
-__global__ __launch_bounds__(1024) void k_select(uint64_t* __restrict__ surv, uint32_t* __restrict__ cnt,
-                                                 float* __restrict__ thr, const float* __restrict__ invq,
-                                                 uint32_t* __restrict__ counters, int k1, float margin, int may_have_empty, int keep_max) {
+__device__ __forceinline__ void select_one_query(const int b, uint64_t* surv, uint32_t* cnt,
+                                                 float* thr, const float* invq,
+                                                 uint32_t* counters, int k1, float margin, int may_have_empty, int keep_max) {
     __shared__ uint32_t hist[16][256];
     __shared__ uint32_t tot[256];
     __shared__ uint64_t pivot_s, or_s[16];
     __shared__ uint32_t sel_digit, sel_need, sel_single, band_s, nout_s;
-    const int b = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     uint64_t* list = surv + (int64_t)b * SURV_CAP;
     const uint32_t raw = cnt[b];
     const int n = raw > (uint32_t)SURV_CAP ? SURV_CAP : (int)raw;
@@ -170,23 +170,30 @@ __global__ __launch_bounds__(1024) void k_select(uint64_t* __restrict__ surv, ui
     if (tid == 0) { cnt[b] = nout_s; thr[b] = tau / invq[b]; }
 }
 
+__global__ __launch_bounds__(1024) void k_select(uint64_t* __restrict__ surv, uint32_t* __restrict__ cnt,
+                                                 float* __restrict__ thr, const float* __restrict__ invq,
+                                                 uint32_t* __restrict__ counters, int k1, float margin, int may_have_empty, int keep_max) {
+    select_one_query((int)blockIdx.x, surv, cnt, thr, invq, counters, k1, margin, may_have_empty, keep_max);
+}
+
 // Exact similarities of the selected candidates: one wavefront per (query, candidate) re-reads the
 // stored row and accumulates dot product and squared norm in fp64 (products of 16-bit values are
 // exact, so this is the cosine of the stored vectors up to fp64 rounding).
 template <int DT>
-__global__ __launch_bounds__(1024) void k_rescore(const void* __restrict__ store_, const float* __restrict__ qf,
-                                                  const double* __restrict__ invq64, const uint64_t* __restrict__ surv,
-                                                  const uint32_t* __restrict__ cnt, double* __restrict__ exact,
+__device__ __forceinline__ void rescore_one_query(const int b, const int part, const int parts,
+                                                  const void* store_, const float* qf,
+                                                  const double* invq64, const uint64_t* surv,
+                                                  const uint32_t* cnt, double* exact,
                                                   int nkb, int exact_stride) {
     // One workgroup per query; 16 lanes per candidate row, so a wavefront works on four rows at a
     // time and every lane has up to eight 16-byte loads in flight.
-    const int b = blockIdx.x, sub = threadIdx.x & 15, grp = threadIdx.x >> 4;   // grp 0..63
+    const int sub = threadIdx.x & 15, grp = threadIdx.x >> 4;   // grp 0..63
     const int n = (int)cnt[b];
     const float* q = qf + (int64_t)b * nkb * KB;
     constexpr int EPC = DT == 0 ? 4 : 8;                 // elements per 16-byte chunk
     const int nch = nkb * KB / EPC;                      // chunks per row
-    // (gridDim.y workgroups share a query: workgroup y takes the candidate groups y, y + gridDim.y, ...)
-    for (int j0 = 64 * (int)blockIdx.y; j0 < n; j0 += 64 * (int)gridDim.y) {   // uniform trip count: the shuffles below need all lanes
+    // (`parts` workgroups share a query: workgroup `part` takes the candidate groups part, part + parts, ...)
+    for (int j0 = 64 * part; j0 < n; j0 += 64 * parts) {   // uniform trip count: the shuffles below need all lanes
         const int j = j0 + grp;
         const bool live = j < n;
         const int32_t id = live ? key_id(surv[(int64_t)b * SURV_CAP + j]) : 0;
@@ -230,6 +237,14 @@ __global__ __launch_bounds__(1024) void k_rescore(const void* __restrict__ store
         for (int o = 8; o > 0; o >>= 1) { dot += __shfl_xor(dot, o, 64); ssq += __shfl_xor(ssq, o, 64); }
         if (live && sub == 0) exact[(int64_t)b * exact_stride + j] = dot * invq64[b] * (1.0 / sqrt(ssq));
     }
+}
+
+template <int DT>
+__global__ __launch_bounds__(1024) void k_rescore(const void* __restrict__ store_, const float* __restrict__ qf,
+                                                  const double* __restrict__ invq64, const uint64_t* __restrict__ surv,
+                                                  const uint32_t* __restrict__ cnt, double* __restrict__ exact,
+                                                  int nkb, int exact_stride) {
+    rescore_one_query<DT>((int)blockIdx.x, (int)blockIdx.y, (int)gridDim.y, store_, qf, invq64, surv, cnt, exact, nkb, exact_stride);
 }
 
 constexpr int RERANK_T = 256;
@@ -293,34 +308,41 @@ __device__ __forceinline__ bool ranks_before(double v, int32_t id, double w, int
 // The lists are short (at most 512 and 256 entries), so both orderings are done by counting: every
 // thread counts how many entries precede its own (each step reads one LDS entry, broadcast to all
 // lanes) and writes its entry to that rank -- two barriers instead of a sorting network.
-__global__ __launch_bounds__(RERANK_T) void k_rerank(const uint64_t* __restrict__ surv, const uint32_t* __restrict__ cnt,
-                                                const double* __restrict__ exact, const float* __restrict__ qstage,
-                                                int k1, int k2, double lambda, int32_t* __restrict__ out_ids,
-                                                float* __restrict__ out_scores, int32_t* __restrict__ cand_ids,
-                                                float* __restrict__ cand_sims, EpsGreedy eg, int exact_stride) {
+// T: lanes of the workgroup that runs it (256, or 1024 inside the fused kernel below; pool entry i belongs
+// to lane i either way, and the block sums add the same four partial sums in the same order).
+template <int T>
+__device__ __forceinline__ void rerank_one_query(const int b, const uint64_t* surv, const uint32_t* cnt,
+                                                const double* exact, const float* qstage,
+                                                int k1, int k2, double lambda, int32_t* out_ids,
+                                                float* out_scores, int32_t* cand_ids,
+                                                float* cand_sims, EpsGreedy eg, int exact_stride) {
     __shared__ double v0[KEEP_MAX], v1[MEM_MAX_K1_INTERNAL];
     __shared__ int32_t i0[KEEP_MAX], i1[MEM_MAX_K1_INTERNAL];
     __shared__ double red[4];
-    const int b = blockIdx.x, tid = threadIdx.x;
+    const int tid = threadIdx.x;
     const int kk = (int)cnt[b];
-    for (int i = tid; i < kk; i += RERANK_T) {
+    for (int i = tid; i < kk; i += T) {
         v0[i] = finite_or_lowest(exact[(int64_t)b * exact_stride + i]);
         i0[i] = key_id(surv[(int64_t)b * SURV_CAP + i]);
     }
     __syncthreads();
     const int k1e = kk < k1 ? kk : k1;
     // ordering 1: the k1e best by (similarity desc, id asc) -> (v1, i1)
-    for (int i = tid; i < kk; i += RERANK_T) {
+    // (SPLIT lanes share an entry when the workgroup has lanes to spare: each counts over every
+    // SPLIT-th other entry and the partial counts are added across the neighbouring lanes)
+    constexpr int SPLIT = T >= 1024 ? 4 : 1;
+    for (int i = tid / SPLIT; i < kk; i += T / SPLIT) {           // trip count uniform within a lane group
         const double v = v0[i];
         const int32_t id = i0[i];
         int rank = 0;
 #pragma unroll 8
-        for (int j = 0; j < kk; ++j) rank += ranks_before(v0[j], i0[j], v, id);
-        if (rank < k1e) { v1[rank] = v; i1[rank] = id; }
+        for (int j = tid % SPLIT; j < kk; j += SPLIT) rank += ranks_before(v0[j], i0[j], v, id);
+        if (SPLIT == 4) { rank += __shfl_xor(rank, 1, 64); rank += __shfl_xor(rank, 2, 64); }
+        if (tid % SPLIT == 0 && rank < k1e) { v1[rank] = v; i1[rank] = id; }
     }
     __syncthreads();
     if (cand_ids)
-        for (int i = tid; i < k1; i += RERANK_T) {
+        for (int i = tid; i < k1; i += T) {
             cand_ids[(int64_t)b * k1 + i] = i < k1e ? i1[i] : -1;
             cand_sims[(int64_t)b * k1 + i] = i < k1e ? (float)v1[i] : -INFINITY;
         }
@@ -351,7 +373,7 @@ __global__ __launch_bounds__(RERANK_T) void k_rerank(const uint64_t* __restrict_
         for (int j = 0; j < k1e; ++j) rank += ranks_before(v0[j], i0[j], score, id);
         if (greedy && rank < k2e) { out_ids[(int64_t)b * k2 + rank] = id; out_scores[(int64_t)b * k2 + rank] = (float)score; }
     }
-    for (int i = k2e + tid; i < k2; i += RERANK_T) {
+    for (int i = k2e + tid; i < k2; i += T) {
         out_ids[(int64_t)b * k2 + i] = -1;
         out_scores[(int64_t)b * k2 + i] = -INFINITY;
         if (eg.explored) eg.explored[(int64_t)b * k2 + i] = 0;
@@ -401,6 +423,35 @@ __global__ __launch_bounds__(RERANK_T) void k_rerank(const uint64_t* __restrict_
             if (eg.explored) eg.explored[(int64_t)b * k2 + j] = explore ? 1 : 0;
         }
     }
+}
+
+
+__global__ __launch_bounds__(RERANK_T) void k_rerank(const uint64_t* __restrict__ surv, const uint32_t* __restrict__ cnt,
+                                                const double* __restrict__ exact, const float* __restrict__ qstage,
+                                                int k1, int k2, double lambda, int32_t* __restrict__ out_ids,
+                                                float* __restrict__ out_scores, int32_t* __restrict__ cand_ids,
+                                                float* __restrict__ cand_sims, EpsGreedy eg, int exact_stride) {
+    rerank_one_query<RERANK_T>((int)blockIdx.x, surv, cnt, exact, qstage, k1, k2, lambda, out_ids, out_scores, cand_ids, cand_sims, eg, exact_stride);
+}
+
+// The last selection, the exact re-scoring and the value filter of one query in one launch (pools of up
+// to 128, one workgroup per query): the three steps hand their results on through the same global
+// buffers as the separate kernels do -- a workgroup's own writes are visible to it after a barrier --
+// so the results are bit for bit those of the three launches, without two launch latencies.
+template <int DT>
+__global__ __launch_bounds__(1024) void k_select_rescore_rerank(
+        uint64_t* __restrict__ surv, uint32_t* __restrict__ cnt, float* __restrict__ thr, const float* __restrict__ invq,
+        uint32_t* __restrict__ counters, int k1, float margin, int may_have_empty, int keep_max,
+        const void* __restrict__ store_, const float* __restrict__ qf, const double* __restrict__ invq64,
+        double* __restrict__ exact, int nkb, int exact_stride,
+        const float* __restrict__ qstage, int k2, double lambda, int32_t* __restrict__ out_ids, float* __restrict__ out_scores,
+        int32_t* __restrict__ cand_ids, float* __restrict__ cand_sims, EpsGreedy eg) {
+    const int b = (int)blockIdx.x;
+    select_one_query(b, surv, cnt, thr, invq, counters, k1, margin, may_have_empty, keep_max);
+    __syncthreads();
+    rescore_one_query<DT>(b, 0, 1, store_, qf, invq64, surv, cnt, exact, nkb, exact_stride);
+    __syncthreads();
+    rerank_one_query<1024>(b, surv, cnt, exact, qstage, k1, k2, lambda, out_ids, out_scores, cand_ids, cand_sims, eg, exact_stride);
 }
 
 }  // namespace evk
