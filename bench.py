@@ -107,8 +107,11 @@ def run_stream(torch, binding, synth):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    # Defaults: the clocks of the GPU settle only after some tens of milliseconds of continuous load (the
+    # densest pass runs 490 us in the first launches, about 600 us from the 7th to the 12th, and levels
+    # out near 515 us after some 25), so the untimed warm-up covers that transient.
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="clustered", choices=["clustered", "tiny", "mid", "large", "stream1m", "stream"])
     ap.add_argument("--batch", type=int, default=0, help="override the workload's query batch size B")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -193,7 +196,9 @@ def main():
     qps = w.B / (ms_per_step * 1e-3)
 
     # separate timing of the three calls (not part of `value`)
-    def timed(fn, reps=10):
+    def timed(fn, reps=50):
+        for _ in range(10):            # back to steady clocks after the idle gap above
+            fn()
         torch.cuda.synchronize()
         a = time.perf_counter()
         for _ in range(reps):
@@ -246,8 +251,9 @@ def main():
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": {"f32": "f32", "bf16": "bf16", "f16": "f16"}[w.dtype], "data": "synthetic",
         "config": {"workload": f"{w.name}: N={w.N} d={w.d} {w.dtype} store / fp32 accumulate, B={w.B} k1={w.k1} "
-                               f"k2={w.k2} lambda={w.lam}; step = append B + retrieve B + update_q B*k2",
-                   "N": w.N, "d": w.d, "B": w.B, "k1": w.k1, "k2": w.k2},
+                               f"k2={w.k2} lambda={w.lam}; step = append B + retrieve B + update_q B*k2 "
+                               f"(the bank holds N entries before the first step and grows by B per step)",
+                   "N": w.N, "N_after_last_step": w.N + (steps + warm) * w.B, "d": w.d, "B": w.B, "k1": w.k1, "k2": w.k2},
         "roofline": roofline, "cpu_baseline": cpu, "breakdown": breakdown,
     }))
     bank.close()
