@@ -318,9 +318,13 @@ int launch_mfma(evomem* h, hipStream_t st, int Bp, const Level& L, int k1, const
     if (groups > (L.ntiles + 7) / 8) groups = (L.ntiles + 7) / 8;
     dim3 grid((unsigned)(8 * nqt * groups)), block(64 * WQ * WR);
     // A pass is expected to keep about k1 * rho rows per query; spread over its tiles that is the
-    // number of survivors a workgroup stages per tile, and it writes them out when half its list is used.
+    // number of survivors a workgroup stages per tile.  It writes its list out at evenly spaced tiles,
+    // as seldom as keeps the expected fill under 55 % of the list (a surplus takes the direct path).
     const double per_tile = L.rho ? (double)k1 * L.rho * QT / L.ntiles : 1.0;
-    int flush_every = (int)(SCAN_LIST_CAP / 2 / (per_tile + 1.0));
+    const int tiles_per_wg = (int)((L.ntiles + 8 * groups - 1) / (8 * groups));
+    int n_flush = (int)std::ceil(tiles_per_wg * (per_tile + 1.0) / (0.55 * SCAN_LIST_CAP));
+    if (n_flush < 1) n_flush = 1;
+    int flush_every = (tiles_per_wg + n_flush - 1) / n_flush;
     if (flush_every < 1) flush_every = 1;
     if (flush_every > 64) flush_every = 64;
     unsigned char* ws = h->ws;
