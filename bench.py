@@ -175,6 +175,14 @@ def main():
         ids, _, _, _ = bank.retrieve(q_dev[s % len(q_dev)], stage, w.k1, w.k2, w.lam, out=out)
         bank.update_q(ids.view(-1), stage, rewards[s % len(rewards)], w.alpha)
 
+    # With fewer than 50 warm-up steps the clocks would still be settling inside the timed region (see the
+    # note at --steps): read-only retrieve calls, which leave the bank and the Q tables as they are, make
+    # up the difference before the warm-up steps.
+    bank.profile_enable(True)        # creates the library's timing events now, not inside the timed region
+    bank.profile_enable(False)
+    settle = max(0, 50 - warm)
+    for s in range(settle):
+        bank.retrieve(q_dev[s % len(q_dev)], stage, w.k1, w.k2, w.lam, out=out)
     for s in range(warm):
         step(s)
     torch.cuda.synchronize()
@@ -248,7 +256,7 @@ def main():
         "metric": "retrieval queries/sec at N=1M,d=1024 + achieved HBM GB/s (% of peak)"
                   if args.workload == "clustered" and not args.batch else f"retrieval queries/sec ({args.workload}, B={w.B})",
         "value": round(qps, 1), "unit": "queries/s", "n_gpus": 1, "steps": steps, "warmup": warm,
-        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "settle_retrieves_before_warmup": settle, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": {"f32": "f32", "bf16": "bf16", "f16": "f16"}[w.dtype], "data": "synthetic",
         "config": {"workload": f"{w.name}: N={w.N} d={w.d} {w.dtype} store / fp32 accumulate, B={w.B} k1={w.k1} "
                                f"k2={w.k2} lambda={w.lam}; step = append B + retrieve B + update_q B*k2 "
