@@ -187,9 +187,9 @@ def main():
         step(s)
     torch.cuda.synchronize()
     # The library's launch timing (events around every scan launch, on its own stream) is switched on
-    # for every fourth timed step only: each event costs about 6 us of idle time on either side of
+    # for every tenth timed step only: each event costs about 6 us of idle time on either side of
     # the launch, which would otherwise lengthen every step by ~35 us.
-    PROFILE_EVERY = 4
+    PROFILE_EVERY = 10
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     for s in range(steps):
