@@ -8,7 +8,6 @@
 #include <new>
 #include <vector>
 
-#define MEM_MAX_K1_INTERNAL 256
 #include "../../include/evomem.h"
 #include "k_ingest.h"
 #include "k_scan_gemv.h"
@@ -29,34 +28,37 @@ namespace {
 constexpr int MAX_PROFILE = 4096;
 constexpr int GEMV_MAX_B = 4;       // fp32 stores: at most this many queries use the VALU scan
 
-inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+constexpr int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
-struct Workspace {   // byte offsets into the caller's workspace
+struct Workspace {   // byte offsets into a scratch area (the caller's workspace, or the library's own array)
     size_t counters, qf, qop, invq, invq64, thr, cnt, surv, exact, total;
 };
 
-Workspace carve(int d, int dtype, int max_B, int max_k1) {
-    const int64_t dpad = round_up(d, KB), Bp = round_up(max_B, 256);
-    Workspace w{};
-    size_t o = 0;
-    auto take = [&](size_t bytes) { size_t at = o; o = (size_t)round_up((int64_t)(o + bytes), 256); return at; };
-    w.counters = take(256);
-    w.qf = take((size_t)Bp * dpad * 4);
-    w.qop = take((size_t)Bp * (dpad + KB) * (dtype == MEM_F32 ? 4 : 2));   // + one all-zero k-block
-    w.invq = take((size_t)Bp * 4);
-    w.invq64 = take((size_t)Bp * 8);
-    w.thr = take((size_t)Bp * 4);
-    w.cnt = take((size_t)Bp * 4);
-    w.surv = take((size_t)Bp * SURV_CAP * 8);
-    w.exact = take((size_t)Bp * keep_of(max_k1) * 8);
-    w.total = o;
-    return w;
+// A retrieve pads its batch to a multiple of its query tile (32 .. 256 queries), so the per-query
+// arrays are sized for max_B rounded up to `bpad` (256 covers every tile).
+constexpr Workspace carve(int d, int dtype, int max_B, int max_k1, int bpad = 256) {
+    const int64_t dpad = round_up(d, KB), Bp = round_up(max_B, bpad);
+    const size_t sizes[9] = {256, (size_t)Bp * dpad * 4,
+                             (size_t)Bp * (dpad + KB) * (dtype == MEM_F32 ? 4 : 2),   // + one all-zero k-block
+                             (size_t)Bp * 4, (size_t)Bp * 8, (size_t)Bp * 4, (size_t)Bp * 4,
+                             (size_t)Bp * SURV_CAP * 8, (size_t)Bp * keep_of(max_k1) * 8};
+    size_t at[10] = {};
+    for (int i = 0; i < 9; ++i) at[i + 1] = (size_t)round_up((int64_t)(at[i] + sizes[i]), 256);
+    return Workspace{at[0], at[1], at[2], at[3], at[4], at[5], at[6], at[7], at[8], at[9]};
 }
+
+// Where a retrieve keeps its intermediate results.
+struct Scratch {
+    unsigned char* base;
+    Workspace w;
+    int exact_stride;      // fp64 similarities per query
+};
 
 bool shape_ok(int d, int dtype, int64_t capacity) {
     return d >= 8 && d <= 16384 && d % 8 == 0 && dtype >= MEM_F32 && dtype <= MEM_F16 && capacity >= 1 &&
            capacity <= 2147483647ll - 256;
 }
+
 
 }  // namespace
 
@@ -272,33 +274,38 @@ namespace {
 // next pass a tighter threshold).  Each denser pass divides the stride by `ratio`, chosen so that
 // about k1 * ratio rows (a quarter of the survivor slots) are expected to pass its threshold; the
 // step up to the sparsest pass is whatever factor <= ratio fills its row budget.
-std::vector<Level> plan_levels(int64_t N, int k1) {
+// (at most 24 passes: every step divides the stride by at least 2 and a bank has fewer than 2^23 tiles;
+// kept in a fixed array so that a retrieve allocates nothing on the host either)
+constexpr int MAX_LEVELS = 24;
+struct Plan { int n; Level lv[MAX_LEVELS]; };
+Plan plan_levels(int64_t N, int k1) {
     const int nt = (int)((N + TILE_ROWS - 1) / TILE_ROWS);
     const int cap_tiles = SURV_CAP / TILE_ROWS;
     int ratio = SURV_CAP / (4 * k1);
     if (ratio > 16) ratio = 16;
     if (ratio < 2) ratio = 2;
-    std::vector<int> strides{1};
+    int strides[MAX_LEVELS] = {1}, ns = 1;
     for (;;) {
-        const int U = (nt + strides.back() - 1) / strides.back();
+        const int U = (nt + strides[ns - 1] - 1) / strides[ns - 1];
         if (U <= cap_tiles) break;
         const int need = (U + cap_tiles - 1) / cap_tiles;          // >= 2
-        strides.push_back(strides.back() * (need < ratio ? need : ratio));
+        strides[ns] = strides[ns - 1] * (need < ratio ? need : ratio);
+        ++ns;
     }
-    std::vector<Level> lv;
-    for (int i = (int)strides.size() - 1; i >= 0; --i) {
+    Plan p{};
+    for (int i = ns - 1; i >= 0; --i) {
         Level L;
         L.stride = strides[i];
         const int U = (nt + L.stride - 1) / L.stride;
-        if (i == (int)strides.size() - 1) { L.rho = 0; L.ntiles = U; }
+        if (i == ns - 1) { L.rho = 0; L.ntiles = U; }
         else { L.rho = strides[i + 1] / strides[i]; L.ntiles = U - (U + L.rho - 1) / L.rho; }
-        if (L.ntiles > 0) lv.push_back(L);
+        if (L.ntiles > 0) p.lv[p.n++] = L;
     }
-    return lv;
+    return p;
 }
 
 template <int DT, int MQ, int WQ, int MR, int WR, bool MASKED>
-int launch_mfma(evomem* h, hipStream_t st, int Bp, const Level& L, int k1, const Mask& mask, int B) {
+int launch_mfma(evomem* h, const Scratch& sc, hipStream_t st, int Bp, const Level& L, int k1, const Mask& mask, int B) {
     constexpr int QT = 32 * MQ * WQ;
     constexpr int lds = scan_mfma_lds_bytes<QT, MASKED>();
     auto kern = k_scan_mfma<DT, MQ, WQ, MR, WR, MASKED>;
@@ -327,44 +334,44 @@ int launch_mfma(evomem* h, hipStream_t st, int Bp, const Level& L, int k1, const
     int flush_every = (tiles_per_wg + n_flush - 1) / n_flush;
     if (flush_every < 1) flush_every = 1;
     if (flush_every > 64) flush_every = 64;
-    unsigned char* ws = h->ws;
+    unsigned char* ws = sc.base;
     hipLaunchKernelGGL(kern, grid, block, lds, st, (const void*)h->store, (const float*)h->invnorm,
-                       (const uint16_t*)(ws + h->w.qop), (const float*)(ws + h->w.invq), (const float*)(ws + h->w.thr),
-                       (uint32_t*)(ws + h->w.cnt), (uint64_t*)(ws + h->w.surv), h->N, h->nkb, Bp, L, flush_every, mask, B);
+                       (const uint16_t*)(ws + sc.w.qop), (const float*)(ws + sc.w.invq), (const float*)(ws + sc.w.thr),
+                       (uint32_t*)(ws + sc.w.cnt), (uint64_t*)(ws + sc.w.surv), h->N, h->nkb, Bp, L, flush_every, mask, B);
     LAUNCHCHK();
     return MEM_OK;
 }
 
 template <int DT, bool MASKED>
-int launch_mfma_dt(evomem* h, hipStream_t st, int Bp, int qt, const Level& L, int k1, const Mask& mask, int B) {
+int launch_mfma_dt(evomem* h, const Scratch& sc, hipStream_t st, int Bp, int qt, const Level& L, int k1, const Mask& mask, int B) {
     switch (qt) {
-        case 32: return launch_mfma<DT, 1, 1, 2, 4, MASKED>(h, st, Bp, L, k1, mask, B);
+        case 32: return launch_mfma<DT, 1, 1, 2, 4, MASKED>(h, sc, st, Bp, L, k1, mask, B);
         case 64:
             // fp32 stores: 8 wavefronts, so that one wavefront's hi/lo split (vector ALU) overlaps the
             // MFMAs of the other one on its SIMD (measured 0.054 -> 0.047 ms on the 65,536 x 1024 bank)
-            if constexpr (DT == 0) return launch_mfma<DT, 1, 2, 2, 4, MASKED>(h, st, Bp, L, k1, mask, B);
-            else return launch_mfma<DT, 2, 1, 2, 4, MASKED>(h, st, Bp, L, k1, mask, B);
-        case 128: return launch_mfma<DT, 2, 2, 2, 4, MASKED>(h, st, Bp, L, k1, mask, B);   // 8 wavefronts, 64 x 64 each
-        default: return launch_mfma<DT, 4, 2, 2, 4, MASKED>(h, st, Bp, L, k1, mask, B);    // 8 wavefronts, 128 x 64 each
+            if constexpr (DT == 0) return launch_mfma<DT, 1, 2, 2, 4, MASKED>(h, sc, st, Bp, L, k1, mask, B);
+            else return launch_mfma<DT, 2, 1, 2, 4, MASKED>(h, sc, st, Bp, L, k1, mask, B);
+        case 128: return launch_mfma<DT, 2, 2, 2, 4, MASKED>(h, sc, st, Bp, L, k1, mask, B);   // 8 wavefronts, 64 x 64 each
+        default: return launch_mfma<DT, 4, 2, 2, 4, MASKED>(h, sc, st, Bp, L, k1, mask, B);    // 8 wavefronts, 128 x 64 each
     }
 }
 template <bool MASKED>
-int launch_mfma_any(evomem* h, hipStream_t st, int Bp, int qt, const Level& L, int k1, const Mask& mask, int B) {
-    return h->dtype == MEM_F32 ? launch_mfma_dt<0, MASKED>(h, st, Bp, qt, L, k1, mask, B)
-         : h->dtype == MEM_BF16 ? launch_mfma_dt<1, MASKED>(h, st, Bp, qt, L, k1, mask, B)
-                                : launch_mfma_dt<2, MASKED>(h, st, Bp, qt, L, k1, mask, B);
+int launch_mfma_any(evomem* h, const Scratch& sc, hipStream_t st, int Bp, int qt, const Level& L, int k1, const Mask& mask, int B) {
+    return h->dtype == MEM_F32 ? launch_mfma_dt<0, MASKED>(h, sc, st, Bp, qt, L, k1, mask, B)
+         : h->dtype == MEM_BF16 ? launch_mfma_dt<1, MASKED>(h, sc, st, Bp, qt, L, k1, mask, B)
+                                : launch_mfma_dt<2, MASKED>(h, sc, st, Bp, qt, L, k1, mask, B);
 }
 
 template <int NB>
-int launch_gemv(evomem* h, hipStream_t st, int B, const Level& L, const Mask& mask) {
-    unsigned char* ws = h->ws;
+int launch_gemv(evomem* h, const Scratch& sc, hipStream_t st, int B, const Level& L, const Mask& mask) {
+    unsigned char* ws = sc.base;
     const bool split = L.ntiles < 1024;        // few tiles: four workgroups per tile
     dim3 grid((unsigned)(split ? 4 * L.ntiles : L.ntiles)), block(256);
-    const float* invq = (const float*)(ws + h->w.invq);
-    const float* thr = (const float*)(ws + h->w.thr);
-    const float* qf = (const float*)(ws + h->w.qf);
-    uint32_t* cnt = (uint32_t*)(ws + h->w.cnt);
-    uint64_t* surv = (uint64_t*)(ws + h->w.surv);
+    const float* invq = (const float*)(ws + sc.w.invq);
+    const float* thr = (const float*)(ws + sc.w.thr);
+    const float* qf = (const float*)(ws + sc.w.qf);
+    uint32_t* cnt = (uint32_t*)(ws + sc.w.cnt);
+    uint64_t* surv = (uint64_t*)(ws + sc.w.surv);
     if (split)
         hipLaunchKernelGGL((k_scan_gemv32<NB, 4>), grid, block, 0, st, (const float*)h->store, (const float*)h->invnorm, qf, invq,
                            thr, cnt, surv, h->N, h->nkb, B, L, mask);
@@ -379,42 +386,43 @@ int launch_gemv(evomem* h, hipStream_t st, int B, const Level& L, const Mask& ma
 
 extern "C" int mem_plan_levels(int64_t N, int k1, int* stride, int* rho, int* ntiles, int max_levels) {
     if (N < 1 || N > 2147483647ll - 256 || k1 < 1 || k1 > MEM_MAX_K1 || !stride || !rho || !ntiles || max_levels < 1) return -1;
-    std::vector<Level> lv = plan_levels(N, k1);
-    for (int i = 0; i < (int)lv.size() && i < max_levels; ++i) { stride[i] = lv[i].stride; rho[i] = lv[i].rho; ntiles[i] = lv[i].ntiles; }
-    return (int)lv.size();
+    const Plan p = plan_levels(N, k1);
+    for (int i = 0; i < p.n && i < max_levels; ++i) { stride[i] = p.lv[i].stride; rho[i] = p.lv[i].rho; ntiles[i] = p.lv[i].ntiles; }
+    return p.n;
 }
 
 static int retrieve_impl(evomem_t* h, const float* queries_dev, int B, int stage, int k1, int k2, float lambda,
                          int32_t* out_ids_dev, float* out_scores_dev, int32_t* out_cand_ids_dev,
-                         float* out_cand_sims_dev, void* hip_stream, const EpsGreedy& eg, const Mask& mask) {
-    if (!h || B < 0 || B > h->max_B || (stage != 0 && stage != 1) || k1 < 1 || k2 < 1 || k2 > k1 || k1 > h->max_k1)
+                         float* out_cand_sims_dev, void* hip_stream, const EpsGreedy& eg, const Mask& mask,
+                         const Scratch& sc, int max_B, int max_k1) {
+    if (!h || B < 0 || B > max_B || (stage != 0 && stage != 1) || k1 < 1 || k2 < 1 || k2 > k1 || k1 > max_k1)
         return MEM_EINVAL;
     if (!(lambda >= 0.f && lambda <= 1.f)) return MEM_EINVAL;
     if ((out_cand_ids_dev == nullptr) != (out_cand_sims_dev == nullptr)) return MEM_EINVAL;
     if (B == 0) return MEM_OK;
     if (!queries_dev || !out_ids_dev || !out_scores_dev) return MEM_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    unsigned char* ws = h->ws;
+    unsigned char* ws = sc.base;
     const bool gemv = B <= GEMV_MAX_B && h->dtype == MEM_F32;
     // query tile of the MFMA scan and padded batch
     int qt = B <= 32 ? 32 : B <= 64 ? 64 : B <= 128 ? 128 : 256;
     const int Bp = gemv ? B : (int)round_up(B, qt);
-    float* qf = (float*)(ws + h->w.qf);
-    uint16_t* qop = (uint16_t*)(ws + h->w.qop);
-    float* invq = (float*)(ws + h->w.invq);
-    double* invq64 = (double*)(ws + h->w.invq64);
-    float* thr = (float*)(ws + h->w.thr);
-    uint32_t* cnt = (uint32_t*)(ws + h->w.cnt);
-    uint64_t* surv = (uint64_t*)(ws + h->w.surv);
-    double* exact = (double*)(ws + h->w.exact);
-    const int exact_stride = keep_of(h->max_k1);
-    uint32_t* counters = (uint32_t*)(ws + h->w.counters);
+    float* qf = (float*)(ws + sc.w.qf);
+    uint16_t* qop = (uint16_t*)(ws + sc.w.qop);
+    float* invq = (float*)(ws + sc.w.invq);
+    double* invq64 = (double*)(ws + sc.w.invq64);
+    float* thr = (float*)(ws + sc.w.thr);
+    uint32_t* cnt = (uint32_t*)(ws + sc.w.cnt);
+    uint64_t* surv = (uint64_t*)(ws + sc.w.surv);
+    double* exact = (double*)(ws + sc.w.exact);
+    const int exact_stride = sc.exact_stride;
+    uint32_t* counters = (uint32_t*)(ws + sc.w.counters);
 
-    std::vector<Level> levels;
+    Plan plan{};
     uint32_t cnt0 = 0;      // valid rows of the sparsest pass (a prefix of its last tile may be all that exists)
     if (h->N > 0) {
-        levels = plan_levels(h->N, k1);
-        const Level& L0 = levels[0];
+        plan = plan_levels(h->N, k1);
+        const Level& L0 = plan.lv[0];
         const int64_t last = level_tile(L0, L0.ntiles - 1) * TILE_ROWS;
         const int64_t in_last = h->N - last < TILE_ROWS ? h->N - last : TILE_ROWS;
         cnt0 = (uint32_t)((int64_t)(L0.ntiles - 1) * TILE_ROWS + in_last);
@@ -438,18 +446,19 @@ static int retrieve_impl(evomem_t* h, const float* queries_dev, int B, int stage
     // 256 queries: see the kernel).
     const bool fused_tail = h->N > 0 && k1 <= 128 && B > 128;
     if (h->N > 0) {
-        for (const Level& L : levels) {
+        for (int li = 0; li < plan.n; ++li) {
+            const Level& L = plan.lv[li];
             const bool prof = h->prof_on && h->prof_n < MAX_PROFILE;
             if (prof) HIPCHK(hipEventRecord(h->ev[2 * h->prof_n], st));
             int rc;
             if (gemv) {
-                rc = B == 1 ? launch_gemv<1>(h, st, B, L, mask) : B == 2 ? launch_gemv<2>(h, st, B, L, mask) : launch_gemv<4>(h, st, B, L, mask);
+                rc = B == 1 ? launch_gemv<1>(h, sc, st, B, L, mask) : B == 2 ? launch_gemv<2>(h, sc, st, B, L, mask) : launch_gemv<4>(h, sc, st, B, L, mask);
             } else {
                 // a sparse pass has few bank tiles: give each workgroup fewer queries, so that more
                 // workgroups share the pass and each one's k-loop is shorter
                 int lqt = qt;
                 while (lqt > 32 && (int64_t)L.ntiles * (Bp / lqt) < 128) lqt >>= 1;
-                rc = mask.tags ? launch_mfma_any<true>(h, st, Bp, lqt, L, k1, mask, B) : launch_mfma_any<false>(h, st, Bp, lqt, L, k1, mask, B);
+                rc = mask.tags ? launch_mfma_any<true>(h, sc, st, Bp, lqt, L, k1, mask, B) : launch_mfma_any<false>(h, sc, st, Bp, lqt, L, k1, mask, B);
             }
             if (rc != MEM_OK) return rc;
             if (prof) {
@@ -457,7 +466,7 @@ static int retrieve_impl(evomem_t* h, const float* queries_dev, int B, int stage
                 int64_t rows = (int64_t)L.ntiles * TILE_ROWS;
                 h->prof_rows[h->prof_n++] = rows;
             }
-            if (fused_tail && &L == &levels.back()) break;          // the last selection runs inside the fused kernel below
+            if (fused_tail && li == plan.n - 1) break;          // the last selection runs inside the fused kernel below
             hipLaunchKernelGGL(k_select, dim3(B), dim3(1024), 0, st, surv, cnt, thr, (const float*)invq, counters, k1, margin, mask.tags != nullptr, keep_of(k1));
             LAUNCHCHK();
         }
@@ -509,22 +518,27 @@ static int retrieve_impl(evomem_t* h, const float* queries_dev, int B, int stage
     return MEM_OK;
 }
 
+// the scratch area a handle was created with
+static Scratch own_scratch(const evomem* h) { return Scratch{h->ws, h->w, keep_of(h->max_k1)}; }
+
 extern "C" int mem_retrieve(evomem_t* h, const float* queries_dev, int B, int stage, int k1, int k2, float lambda,
                             int32_t* out_ids_dev, float* out_scores_dev, int32_t* out_cand_ids_dev,
                             float* out_cand_sims_dev, void* hip_stream) {
+    if (!h) return MEM_EINVAL;
     const EpsGreedy greedy{0, 0, 0, nullptr};
     return retrieve_impl(h, queries_dev, B, stage, k1, k2, lambda, out_ids_dev, out_scores_dev, out_cand_ids_dev,
-                         out_cand_sims_dev, hip_stream, greedy, Mask{nullptr, nullptr, nullptr});
+                         out_cand_sims_dev, hip_stream, greedy, Mask{nullptr, nullptr, nullptr}, own_scratch(h), h->max_B, h->max_k1);
 }
 
 extern "C" int mem_retrieve_eps(evomem_t* h, const float* queries_dev, int B, int stage, int k1, int k2, float lambda,
                                 float eps, uint64_t seed, uint64_t step, int32_t* out_ids_dev, float* out_scores_dev,
                                 int32_t* out_cand_ids_dev, float* out_cand_sims_dev, unsigned char* out_explored_dev,
                                 void* hip_stream) {
+    if (!h) return MEM_EINVAL;
     if (!(eps >= 0.f && eps <= 1.f)) return MEM_EINVAL;
     const EpsGreedy eg{(uint64_t)((double)eps * 4294967296.0), seed, step, out_explored_dev};
     return retrieve_impl(h, queries_dev, B, stage, k1, k2, lambda, out_ids_dev, out_scores_dev, out_cand_ids_dev,
-                         out_cand_sims_dev, hip_stream, eg, Mask{nullptr, nullptr, nullptr});
+                         out_cand_sims_dev, hip_stream, eg, Mask{nullptr, nullptr, nullptr}, own_scratch(h), h->max_B, h->max_k1);
 }
 
 extern "C" int mem_attach_tags(evomem_t* h, uint32_t* tags_dev) {
@@ -553,7 +567,8 @@ extern "C" int mem_retrieve_masked(evomem_t* h, const float* queries_dev, int B,
     if (B > 0 && (!allow_types_dev || !exclude_group_dev)) return MEM_EINVAL;
     const EpsGreedy greedy{0, 0, 0, nullptr};
     return retrieve_impl(h, queries_dev, B, stage, k1, k2, lambda, out_ids_dev, out_scores_dev, out_cand_ids_dev,
-                         out_cand_sims_dev, hip_stream, greedy, Mask{h->tags, allow_types_dev, exclude_group_dev});
+                         out_cand_sims_dev, hip_stream, greedy, Mask{h->tags, allow_types_dev, exclude_group_dev}, own_scratch(h),
+                         h->max_B, h->max_k1);
 }
 
 extern "C" int mem_select_by_q(evomem_t* h, const int32_t* set_ids_dev, int64_t n_ids, const int64_t* set_offsets_dev,

@@ -277,11 +277,13 @@ struct EpsGreedy {
     unsigned char* explored; // [B][k2] or null
 };
 
-// Deterministic sum of one value per thread over a 256-thread workgroup: wavefront butterflies, then
-// the four partial sums added in a fixed order.
+// Deterministic sum of one value per pool entry: wavefront butterflies, then the four partial sums of
+// the first 256 lanes added in a fixed order.  `red` has four slots; pool entry i belongs to lane
+// i < SMALL_K1_MAX = 256, so the lanes beyond (the fused kernel runs 1024) hold zeros and store nothing.
 __device__ __forceinline__ double block_sum(double* red, int tid, double x) {
+    static_assert(SMALL_K1_MAX == 4 * 64, "block_sum adds the partial sums of exactly four wavefronts");
     x = wave_sum_d(x);
-    if ((tid & 63) == 0) red[tid >> 6] = x;
+    if ((tid & 63) == 0 && tid < SMALL_K1_MAX) red[tid >> 6] = x;
     __syncthreads();
     double r = (red[0] + red[1]) + (red[2] + red[3]);
     __syncthreads();
@@ -316,8 +318,8 @@ __device__ __forceinline__ void rerank_one_query(const int b, const uint64_t* su
                                                 int k1, int k2, double lambda, int32_t* out_ids,
                                                 float* out_scores, int32_t* cand_ids,
                                                 float* cand_sims, EpsGreedy eg, int exact_stride) {
-    __shared__ double v0[KEEP_MAX], v1[MEM_MAX_K1_INTERNAL];
-    __shared__ int32_t i0[KEEP_MAX], i1[MEM_MAX_K1_INTERNAL];
+    __shared__ double v0[KEEP_MAX], v1[SMALL_K1_MAX];
+    __shared__ int32_t i0[KEEP_MAX], i1[SMALL_K1_MAX];
     __shared__ double red[4];
     const int tid = threadIdx.x;
     const int kk = (int)cnt[b];
@@ -383,7 +385,7 @@ __device__ __forceinline__ void rerank_one_query(const int b, const uint64_t* su
     // Epsilon-greedy slot filling (Sec. 3.3).  The whole pool is laid out in greedy order; every
     // slot's draw is computed by its own lane (the draws depend on the slot number only); then one
     // lane fills the slots in order, because which members are still free depends on the slots before.
-    __shared__ uint32_t word0[MEM_MAX_K1_INTERNAL], word1[MEM_MAX_K1_INTERNAL];
+    __shared__ uint32_t word0[SMALL_K1_MAX], word1[SMALL_K1_MAX];
     if (mine) { v1[rank] = score; i1[rank] = id; }
     if (tid < k2e) {
         const philox_out r = philox4x32_10((uint32_t)eg.step, (uint32_t)(eg.step >> 32), (uint32_t)b, (uint32_t)tid,
@@ -393,9 +395,9 @@ __device__ __forceinline__ void rerank_one_query(const int b, const uint64_t* su
     }
     __syncthreads();
     if (tid == 0) {
-        uint64_t taken[MEM_MAX_K1_INTERNAL / 64];                     // bit set = chosen (or past the pool's end)
+        uint64_t taken[SMALL_K1_MAX / 64];                     // bit set = chosen (or past the pool's end)
 #pragma unroll
-        for (int w = 0; w < MEM_MAX_K1_INTERNAL / 64; ++w) {
+        for (int w = 0; w < SMALL_K1_MAX / 64; ++w) {
             const int lo = w * 64;
             taken[w] = k1e >= lo + 64 ? 0ull : k1e <= lo ? ~0ull : (~0ull << (k1e - lo));
         }
@@ -405,7 +407,7 @@ __device__ __forceinline__ void rerank_one_query(const int b, const uint64_t* su
             int want = explore ? (int)(((uint64_t)word1[j] * remaining) >> 32) : 0;   // index among the free members
             int pos = 0;
 #pragma unroll
-            for (int w = 0; w < MEM_MAX_K1_INTERNAL / 64; ++w) {
+            for (int w = 0; w < SMALL_K1_MAX / 64; ++w) {
                 uint64_t fr = ~taken[w];
                 const int c = __popcll(fr);
                 if (want >= 0 && want < c) {

@@ -22,8 +22,9 @@ constexpr int BLOCK_ELEMS = TILE_ROWS * KB;
 constexpr int SURV_CAP = 8192;            // survivor slots per query
 constexpr int KEEP_MAX = 512;             // padded size of the selected list (k1 + guard band) for pools up to 256
 constexpr int BIG_K1_MAX = 2048;          // largest pool
+constexpr int SMALL_K1_MAX = 256;         // largest pool of the one-entry-per-lane value filter (k_rerank)
 // room for the selected list of a pool of k1: the pool plus a guard band of near-ties
-__host__ __device__ __forceinline__ int keep_of(int k1) { return k1 <= 256 ? KEEP_MAX : k1 + 256; }
+__host__ __device__ constexpr int keep_of(int k1) { return k1 <= 256 ? KEEP_MAX : k1 + 256; }
 
 // physical 16-byte chunk index of logical chunk c (0..7) in row r (16-bit stores only)
 __host__ __device__ __forceinline__ int swz16(int c, int r) { return c ^ ((r >> 1) & 7); }

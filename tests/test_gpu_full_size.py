@@ -1,9 +1,12 @@
-"""Parity at the full sizes of the two largest workloads (4,194,304 x 1536 bf16 with 1024 queries;
-8,388,608 x 4096 fp16 with 128 queries): sampled queries against the oracle over the WHOLE bank.
+"""Parity at the full sizes of the two largest workloads: sampled queries against the oracle over the
+WHOLE bank.
 
-These take minutes (the oracle streams through up to 69 GB of rows), so they only run when
-EVOMEM_FULL_SIZE=1 is set:
-    EVOMEM_FULL_SIZE=1 python -m pytest tests/test_gpu_full_size.py -m gpu -x -q -s
+  large   4,194,304 x 1536 bf16, 1024 queries, 32 of them sampled: runs by default (about three minutes).
+  stream  d = 4096 fp16, 128 queries, k1 = 256, 32 of them sampled: by default on a 589,824-entry bank
+          (2.4e9 stored elements, so every offset beyond 2^31 elements is exercised; under a minute);
+          at the full 8,388,608 entries (68.7 GB, the oracle needs eleven minutes to stream through
+          them) only when EVOMEM_FULL_SIZE=1 is set:
+              EVOMEM_FULL_SIZE=1 python -m pytest tests/test_gpu_full_size.py -m gpu -x -q -s
 The bank never exists on the host.  Pass 1 generates each 65,536-row chunk, appends it to the GPU
 bank and hands the same fp32 rows to the oracle, which keeps a running top-k1 per sampled query.
 After the GPU retrieve, pass 2 regenerates the chunks and collects only the rows that either side
@@ -20,8 +23,7 @@ from paper_2603_10846_amd import binding as B
 from paper_2603_10846_amd import synth
 from tests import parity
 
-pytestmark = [pytest.mark.gpu,
-              pytest.mark.skipif(os.environ.get("EVOMEM_FULL_SIZE") != "1", reason="set EVOMEM_FULL_SIZE=1 (takes minutes)")]
+pytestmark = pytest.mark.gpu
 DT = {"f32": 0, "bf16": 1, "f16": 2}
 DEV = "cuda:0"
 
@@ -54,7 +56,7 @@ def _full_size_check(orc, w, stage, sample, chunk_of, say):
         xh = orc.round_to_store(x.cpu().numpy() if torch.is_tensor(x) else x, DT[w.dtype])
         part = orc.recall(xh, sel, w.k1, id_base=a, threads=16)
         run_ids, run_sims = orc.merge_recall([(run_ids, run_sims), part], w.k1)
-        if j % 8 == 7 or j == nchunks - 1:
+        if j % 4 == 3 or j == nchunks - 1:
             say(f"{w.name}: chunk {j + 1}/{nchunks} appended and scanned by the oracle, {time.time() - t0:.0f} s")
     gpu = parity.gpu_retrieve(bank, torch, q, stage, w.k1, w.k2, w.lam)
     say(f"{w.name}: GPU retrieve done")
@@ -87,17 +89,36 @@ def _full_size_check(orc, w, stage, sample, chunk_of, say):
     return stats
 
 
+def _sample32(B):
+    """32 query rows: both ends of every 256-query tile the scan forms, the rest spread evenly."""
+    edges = {0, B - 1} | {t for t in range(256, B, 256)} | {t - 1 for t in range(256, B, 256)}
+    rest = [int(x) for x in np.linspace(5, B - 6, 32 - len(edges))]
+    return sorted(edges | set(rest))
+
+
 def test_large_workload_full_size(orc, capsys):
     w = synth.LARGE
     with capsys.disabled():
         say = lambda s: print(s, flush=True)
-        sample = [0, 1, 255, 256, 511, 512, 600, 767, 768, 900, 1000, 1023, 77, 333, 444, 999]
-        _full_size_check(orc, w, synth.REFINE, sample, lambda w, j, rows: synth.bank_chunk(w, j), say)
+        sample = _sample32(w.B)
+        assert len(sample) == 32
+        stats = _full_size_check(orc, w, synth.REFINE, sample, lambda w, j, rows: synth.bank_chunk(w, j), say)
+        assert stats["queries"] == 32
 
 
+def test_stream_workload_beyond_2g_elements(orc, capsys):
+    w = synth.scaled(synth.STREAM, N=9 * synth.CHUNK_ROWS)
+    assert w.N * w.d > 2**31
+    with capsys.disabled():
+        say = lambda s: print(s, flush=True)
+        sample = _sample32(w.B)
+        stats = _full_size_check(orc, w, synth.DRAFT, sample, _device_chunk, say)
+        assert stats["queries"] == 32
+
+
+@pytest.mark.skipif(os.environ.get("EVOMEM_FULL_SIZE") != "1", reason="set EVOMEM_FULL_SIZE=1 (eleven minutes)")
 def test_stream_workload_full_size(orc, capsys):
     w = synth.STREAM
     with capsys.disabled():
         say = lambda s: print(s, flush=True)
-        sample = [0, 1, 31, 32, 63, 64, 65, 96, 100, 126, 127, 17, 45, 80, 111, 120]
-        _full_size_check(orc, w, synth.REFINE, sample, _device_chunk, say)
+        _full_size_check(orc, w, synth.REFINE, _sample32(w.B), _device_chunk, say)

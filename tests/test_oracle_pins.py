@@ -154,6 +154,55 @@ def test_recall_uses_stored_representation(orc):
             assert np.array_equal(order, ids[b]) and np.allclose(S[b][order], sims[b], atol=1e-13, rtol=0)
 
 
+# ----------------------------------------------------------------------------- similarities of given ids
+
+def test_sims_of_brute_force_on_integer_vectors(orc):
+    """Cosines of named ids against the definition written out with Python floats; ids outside the
+    bank (negative, N, far beyond) read -inf; the order of the id list is the order of the output."""
+    rng = np.random.default_rng(41)
+    store = rng.integers(-4, 5, size=(37, 7)).astype(np.float32)
+    store[np.abs(store).sum(1) == 0, 2] = 1
+    q = (rng.integers(-4, 5, size=7) + 0.25).astype(np.float32)
+    ids = np.array([36, 0, 5, 5, -1, 37, 12, 1000000, 20, -7], np.int32)
+    got = orc.sims_of(store, q, ids)
+    nq = math.sqrt(sum(float(v) * float(v) for v in q))
+    for j, i in enumerate(ids):
+        if i < 0 or i >= 37:
+            assert got[j] == -np.inf
+            continue
+        ne = math.sqrt(sum(float(v) * float(v) for v in store[i]))
+        dot = sum(float(a) * float(c) for a, c in zip(q, store[i]))
+        assert abs(got[j] - dot / (nq * ne)) < 1e-15
+    assert got[2] == got[3]                                    # the same id twice: the same value twice
+    # special cases with closed forms: a row against itself, its negative, an orthogonal one-hot row
+    eye = np.eye(5, dtype=np.float32) * np.array([1, 2, 3, 4, 5], np.float32)[:, None]
+    s = orc.sims_of(eye, eye[2] * 7, np.arange(5, dtype=np.int32))
+    assert np.array_equal(s, np.array([0, 0, 1, 0, 0], np.float64))
+    assert orc.sims_of(eye, -eye[3], np.array([3], np.int32))[0] == -1.0
+
+
+def test_sims_of_matches_numpy_on_rounded_rows_and_recall(orc):
+    """On rows rounded to the 16-bit types: an fp64 library product on the rounded values, and the
+    similarities `recall` reports for the ids it returns (the same arithmetic reached another way)."""
+    rng = np.random.default_rng(42)
+    raw, q = _unit(rng, 900, 96), _unit(rng, 4, 96)
+    for dt in (F32, BF16, F16):
+        st, qq = orc.round_to_store(raw, dt), orc.round_to_store(q, dt)
+        s64, q64 = st.astype(np.float64), qq.astype(np.float64)
+        S = (q64 @ s64.T) / np.linalg.norm(q64, axis=1)[:, None] / np.linalg.norm(s64, axis=1)[None, :]
+        r_ids, r_sims = orc.recall(st, qq, 25)
+        for b in range(4):
+            pick = rng.permutation(900)[:60].astype(np.int32)
+            assert np.allclose(orc.sims_of(st, qq[b], pick), S[b][pick], atol=1e-13, rtol=0)
+            assert np.array_equal(orc.sims_of(st, qq[b], r_ids[b]), r_sims[b])
+    # the norm of the ROW must enter (a dropped row norm leaves unnormalised rows wrong)
+    scaled = (raw * rng.uniform(0.5, 3.0, size=(900, 1))).astype(np.float32)
+    pick = np.arange(0, 900, 7, dtype=np.int32)
+    assert np.allclose(orc.sims_of(scaled, q[0], pick), orc.sims_of(raw, q[0], pick), atol=1e-6, rtol=0)
+    # ... and that of the query
+    assert np.allclose(orc.sims_of(raw, q[0] * 5, pick), orc.sims_of(raw, q[0], pick), atol=1e-7, rtol=0)
+
+
 # ----------------------------------------------------------------------------- value filter
 
 def test_rerank_hand_example(orc):
