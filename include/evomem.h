@@ -108,6 +108,24 @@ int mem_retrieve(evomem_t* h, const float* queries_dev, int B, int stage, int k1
                  int32_t* out_cand_ids_dev, float* out_cand_sims_dev, void* hip_stream);
 
 /*
+ * mem_retrieve for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc) and so cannot size and bring a workspace of their
+ * own: the same call, same arguments, same results bit for bit, but every intermediate result lives
+ * in an array that is part of the library itself (5.3 MB per GPU, held while the library is loaded)
+ * instead of the workspace given to mem_create, which this call never touches.  It allocates nothing
+ * on the device or through any allocating routine.
+ * Limits: B <= 64, k1 <= 256, d <= 2048 (after padding to a multiple of 64); beyond them MEM_EINVAL.
+ * The handle's device must be the current device (MEM_ESTATE otherwise).  The first call on a device
+ * looks the array's address up and enqueues a small kernel that clears its counter block.
+ * All handles and streams of a process share the one array of a GPU: calls that overlap on one GPU
+ * race; calls ordered on one stream (or otherwise serialised) do not.  Queries whose survivor list
+ * overflows are counted inside the array, not in the handle's mem_counters.
+ */
+int mem_retrieve_static(evomem_t* h, const float* queries_dev, int B, int stage, int k1, int k2,
+                        float lambda, int32_t* out_ids_dev, float* out_scores_dev,
+                        int32_t* out_cand_ids_dev, float* out_cand_sims_dev, void* hip_stream);
+
+/*
  * Retrieve with epsilon-greedy selection of the final items (Sec. 3.3, Stage 1: the drafting
  * context is drawn from the pool C(x) by an epsilon-greedy policy over Q_1; Sec. 4.4 uses the same
  * policy for both stages).  The pool and the scores are those of mem_retrieve; the k2 slots are

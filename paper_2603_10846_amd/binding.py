@@ -32,6 +32,8 @@ SYMBOLS = {
                              C.POINTER(C.c_int64), C.c_void_p]),
     "mem_retrieve": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_float,
                                C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "mem_retrieve_static": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_float,
+                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "mem_retrieve_eps": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_float, C.c_float,
                                    C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                    C.c_void_p]),
@@ -167,6 +169,14 @@ class MemoryBank:
         _check(self.lib.mem_retrieve(self.h, _ptr(queries), B, stage, k1, k2, lam, _ptr(ids), _ptr(scores),
                                      _ptr(cid), _ptr(csim), _stream()), "mem_retrieve")
         return ids, scores, cid, csim
+
+    def retrieve_static(self, queries: torch.Tensor, stage: int, k1: int, k2: int, lam: float, out):
+        """mem_retrieve with the library's built-in scratch array; `out` = (ids, scores, cand_ids or None,
+        cand_sims or None) are the caller's tensors: nothing is allocated here or in the library."""
+        ids, scores, cid, csim = out
+        _check(self.lib.mem_retrieve_static(self.h, _ptr(queries), queries.shape[0], stage, k1, k2, lam, _ptr(ids),
+                                            _ptr(scores), _ptr(cid), _ptr(csim), _stream()), "mem_retrieve_static")
+        return out
 
     def retrieve_eps(self, queries: torch.Tensor, stage: int, k1: int, k2: int, lam: float, eps: float, seed: int,
                      step: int, want_candidates: bool = False):

@@ -54,6 +54,12 @@ struct Scratch {
     int exact_stride;      // fp64 similarities per query
 };
 
+// Limits of mem_retrieve_static and the library's own scratch array for it (see the header).
+constexpr int STATIC_MAX_B = 64, STATIC_MAX_K1 = 256, STATIC_MAX_D = 2048;
+constexpr Workspace STATIC_W = carve(STATIC_MAX_D, MEM_F32, STATIC_MAX_B, STATIC_MAX_K1, STATIC_MAX_B);
+constexpr size_t STATIC_SCRATCH_BYTES = STATIC_W.total;
+static_assert(STATIC_SCRATCH_BYTES <= (6u << 20), "the built-in scratch array is meant to stay small");
+
 bool shape_ok(int d, int dtype, int64_t capacity) {
     return d >= 8 && d <= 16384 && d % 8 == 0 && dtype >= MEM_F32 && dtype <= MEM_F16 && capacity >= 1 &&
            capacity <= 2147483647ll - 256;
@@ -528,6 +534,40 @@ extern "C" int mem_retrieve(evomem_t* h, const float* queries_dev, int B, int st
     const EpsGreedy greedy{0, 0, 0, nullptr};
     return retrieve_impl(h, queries_dev, B, stage, k1, k2, lambda, out_ids_dev, out_scores_dev, out_cand_ids_dev,
                          out_cand_sims_dev, hip_stream, greedy, Mask{nullptr, nullptr, nullptr}, own_scratch(h), h->max_B, h->max_k1);
+}
+
+// The library's own scratch area for mem_retrieve_static: one array per GPU, in that GPU's memory for
+// as long as the library is loaded.  In host code the array's name only stands for the symbol; its
+// device address is looked up once per device and kept.
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+static unsigned char* scratch_ptr[16] = {};
+
+__global__ void k_clear_words(uint32_t* p, int n) {
+    for (int i = threadIdx.x; i < n; i += blockDim.x) p[i] = 0u;
+}
+
+extern "C" int mem_retrieve_static(evomem_t* h, const float* queries_dev, int B, int stage, int k1, int k2, float lambda,
+                                   int32_t* out_ids_dev, float* out_scores_dev, int32_t* out_cand_ids_dev,
+                                   float* out_cand_sims_dev, void* hip_stream) {
+    if (!h) return MEM_EINVAL;
+    if (h->nkb * KB > STATIC_MAX_D) return MEM_EINVAL;            // B and k1 are checked against their limits below
+    int cur = -1;
+    HIPCHK(hipGetDevice(&cur));
+    if (cur != h->device || cur < 0 || cur >= 16) return MEM_ESTATE;
+    if (!scratch_ptr[cur]) {                                      // first call on this device
+        unsigned char* p = nullptr;
+        HIPCHK(hipGetSymbolAddress(reinterpret_cast<void**>(&p), HIP_SYMBOL(scratch)));
+        if (!p) return MEM_EHIP;
+        // the counter block must start at zero; everything else is written before it is read in every call
+        hipLaunchKernelGGL(k_clear_words, dim3(1), dim3(64), 0, static_cast<hipStream_t>(hip_stream),
+                           reinterpret_cast<uint32_t*>(p + STATIC_W.counters), 64);
+        LAUNCHCHK();
+        scratch_ptr[cur] = p;
+    }
+    const EpsGreedy greedy{0, 0, 0, nullptr};
+    return retrieve_impl(h, queries_dev, B, stage, k1, k2, lambda, out_ids_dev, out_scores_dev, out_cand_ids_dev,
+                         out_cand_sims_dev, hip_stream, greedy, Mask{nullptr, nullptr, nullptr},
+                         Scratch{scratch_ptr[cur], STATIC_W, keep_of(STATIC_MAX_K1)}, STATIC_MAX_B, STATIC_MAX_K1);
 }
 
 extern "C" int mem_retrieve_eps(evomem_t* h, const float* queries_dev, int B, int stage, int k1, int k2, float lambda,
