@@ -39,6 +39,116 @@ def measured_traffic(workload):
     return int(fields["traffic_bytes_per_launch"])
 
 
+MFMA_PEAK_TFLOPS = 2500.0
+
+
+def time_calls(torch, fn, reps, warm=10):
+    """Average milliseconds of fn() over `reps` calls after `warm` untimed ones (host clock around a synchronised region)."""
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    a = time.perf_counter()
+    for _ in range(reps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - a) * 1e3 / reps
+
+
+def retrieve_figures(torch, bank, q, stage, w, elem, reps=30):
+    """Whole-retrieve time and the densest scan pass of a retrieve (the library's HIP events around that
+    launch, on the stream it runs on) for one workload shape; the bank is left as it is."""
+    B = q.shape[0]
+    out = (torch.empty((B, w.k2), dtype=torch.int32, device=q.device),
+           torch.empty((B, w.k2), dtype=torch.float32, device=q.device), None, None)
+    call = lambda: bank.retrieve(q, stage, w.k1, w.k2, w.lam, out=out)
+    ms = time_calls(torch, call, reps)
+    bank.profile_read()
+    bank.profile_enable(True)
+    for _ in range(5):
+        call()
+    prof = bank.profile_read()
+    bank.profile_enable(False)
+    max_rows = max(r for _, r in prof)
+    dense = [t for t, r in prof if r == max_rows]
+    dense_ms = float(np.mean(dense))
+    gbps = max_rows * w.d * elem / (dense_ms * 1e-3) / 1e9
+    tflops = 2.0 * B * max_rows * w.d / (dense_ms * 1e-3) / 1e12
+    return {"B": B, "retrieve_ms": round(ms, 4), "queries_per_s": round(B / (ms * 1e-3), 1),
+            "densest_pass_ms": round(dense_ms, 4), "densest_pass_rows": int(max_rows),
+            "densest_pass_GBps": round(gbps, 1), "hbm_frac": round(gbps / HBM_PEAK_GBS, 4),
+            "mfma_tflops": round(tflops, 1), "mfma_frac": round(tflops / MFMA_PEAK_TFLOPS, 4),
+            "whole_retrieve_store_GBps": round(bank.size() * w.d * elem / (ms * 1e-3) / 1e9, 1)}
+
+
+def read_ceiling(torch, bank, reps=20):
+    """GB/s of a read-only pass over the same stored rows (the library's probe kernel)."""
+    chk = torch.zeros(1, dtype=torch.int32, device=bank.device)
+    nbytes = [0]
+
+    def call():
+        nbytes[0] = bank.read_probe(chk)
+    ms = time_calls(torch, call, reps, warm=5)
+    return {"kernel": "k_read_probe (16-byte loads, every stored byte once)", "bytes": nbytes[0], "ms": round(ms, 4),
+            "GBps": round(nbytes[0] / (ms * 1e-3) / 1e9, 1), "frac_of_peak": round(nbytes[0] / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+
+
+def other_configs(torch, binding, synth, clustered_bank, clustered_w):
+    """Quick figures for the other workload shapes (not part of `value`): the clustered bank at smaller
+    batches, the mid bank, the streaming shape at 1M entries (with a 65,536-entry append) and the large
+    batched bank.  Rows of the two big banks are seeded normalised Gaussians generated on the device."""
+    dev = torch.device("cuda:0")
+    todev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    res = []
+    for B in (1, 64):
+        w = synth.scaled(clustered_w, B=B)
+        r = retrieve_figures(torch, clustered_bank, todev(synth.queries(w)), synth.DRAFT, w, 2)
+        res.append({"workload": f"clustered bank, B={B}", **r})
+    # mid: fp32 rows
+    w = synth.MID
+    bank = binding.MemoryBank(w.d, w.dtype, w.N, max_B=w.B, max_k1=w.k1)
+    qtab = synth.q_tables(w)
+    bank.append(todev(synth.bank(w)), todev(qtab[0]), todev(qtab[1]))
+    r = retrieve_figures(torch, bank, todev(synth.queries(w)), synth.DRAFT, w, 4, reps=50)
+    res.append({"workload": f"mid: N={w.N} d={w.d} f32, B={w.B} k1={w.k1} k2={w.k2}", **r,
+                "note": "a pass this short is over-stated by the events' own idle time; see the kernel trace under profiles/"})
+    bank.close()
+    del bank
+    g = torch.Generator(device=dev).manual_seed(synth.SEED + 77)
+
+    def rows(n, d):
+        x = torch.randn((n, d), device=dev, generator=g)
+        return x / x.norm(dim=1, keepdim=True)
+    # stream shape at 1M entries, plus one 65,536-entry append and the update of the returned ids
+    w = synth.scaled(synth.STREAM, N=1048576)
+    bank = binding.MemoryBank(w.d, w.dtype, w.N + 40 * synth.CHUNK_ROWS, max_B=w.B, max_k1=w.k1)
+    for _ in range(w.N // synth.CHUNK_ROWS):
+        bank.append(rows(synth.CHUNK_ROWS, w.d))
+    r = retrieve_figures(torch, bank, rows(w.B, w.d), synth.REFINE, w, 2, reps=20)
+    chunk = rows(synth.CHUNK_ROWS, w.d)
+    ap_ms = time_calls(torch, lambda: bank.append(chunk), 30, warm=5)       # the bank grows by 35 chunks here
+    ids = torch.randint(0, w.N, (w.B * w.k2,), device=dev, generator=g, dtype=torch.int32)
+    rew = (torch.rand(w.B * w.k2, device=dev, generator=g) < 0.2).float()
+    up_ms = time_calls(torch, lambda: bank.update_q(ids, synth.REFINE, rew, w.alpha), 50)
+    ap_bytes = synth.CHUNK_ROWS * w.d * (4 + 2)
+    res.append({"workload": f"stream shape at N={w.N}: d={w.d} f16, B={w.B} k1={w.k1} k2={w.k2}", **r,
+                "append_65536_ms": round(ap_ms, 4), "append_GBps": round(ap_bytes / (ap_ms * 1e-3) / 1e9, 1),
+                "append_hbm_frac": round(ap_bytes / (ap_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4), "update_q_4096_ms": round(up_ms, 4)})
+    bank.close()
+    del bank, chunk
+    torch.cuda.empty_cache()
+    # large batched bank
+    w = synth.LARGE
+    bank = binding.MemoryBank(w.d, w.dtype, w.N, max_B=w.B, max_k1=w.k1)
+    for _ in range(w.N // synth.CHUNK_ROWS):
+        bank.append(rows(synth.CHUNK_ROWS, w.d))
+    r = retrieve_figures(torch, bank, rows(w.B, w.d), synth.REFINE, w, 2, reps=10)
+    zipf, rew = (todev(a) for a in synth.zipf_update(w))                     # 16,384 ids, Zipf(1.1): one id about 2,000 times
+    up_ms = time_calls(torch, lambda: bank.update_q(zipf, synth.REFINE, rew, w.alpha), 50)
+    res.append({"workload": f"large: N={w.N} d={w.d} bf16, B={w.B} k1={w.k1} k2={w.k2}", **r, "update_q_16384_ms": round(up_ms, 4)})
+    bank.close()
+    return res
+
+
 def run_stream(torch, binding, synth):
     """The growing bank: starts at 1M entries and grows to 8M by 64K-entry appends (d = 4096, fp16
     store); every step appends a chunk, retrieves for B = 128 fresh queries (k1 = 256, k2 = 32,
@@ -115,6 +225,7 @@ def main():
     ap.add_argument("--workload", default="clustered", choices=["clustered", "tiny", "mid", "large", "stream1m", "stream"])
     ap.add_argument("--batch", type=int, default=0, help="override the workload's query batch size B")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-configs", action="store_true", help="skip the quick figures for the other workload shapes")
     ap.add_argument("--cpu-queries", type=int, default=0, help="oracle sample size (0: 16 per thread, at most B)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy five times (reference for HBM counters)")
@@ -248,9 +359,21 @@ def main():
         res = orc.retrieve(rounded, qs, qtab[stage], w.k1, w.k2, float(np.float32(w.lam)), threads=threads)
         orc.update_q32(qtab[stage], res["ids"].reshape(-1), np.zeros(res["ids"].size, np.float32), w.alpha)
         el = time.perf_counter() - a
+        n1 = min(2, nq)
+        a = time.perf_counter()
+        orc.retrieve(rounded, qs[:n1], qtab[stage], w.k1, w.k2, float(np.float32(w.lam)), threads=1)
+        el1 = time.perf_counter() - a
         cpu = {"value": round(nq / el, 3), "unit": "queries/s", "cores": threads, "kind": "oracle",
                "sample": f"{nq} of the {w.B} queries of one step over the full {w.N}-entry bank "
-                         f"(recall + value filter + update), {el:.1f} s"}
+                         f"(recall + value filter + update), {el:.1f} s",
+               "single_thread": {"value": round(n1 / el1, 3), "unit": "queries/s", "sample": f"{n1} queries, {el1:.1f} s"},
+               "nproc": os.cpu_count(), "openmp_max_threads": orc.max_threads()}
+        del rounded
+
+    ceiling = read_ceiling(torch, bank)
+    configs = None
+    if args.workload == "clustered" and not args.batch and not args.no_other_configs:
+        configs = other_configs(torch, binding, synth, bank, w)
 
     print(json.dumps({
         "metric": "retrieval queries/sec at N=1M,d=1024 + achieved HBM GB/s (% of peak)"
@@ -262,7 +385,8 @@ def main():
                                f"k2={w.k2} lambda={w.lam}; step = append B + retrieve B + update_q B*k2 "
                                f"(the bank holds N entries before the first step and grows by B per step)",
                    "N": w.N, "N_after_last_step": w.N + (steps + warm) * w.B, "d": w.d, "B": w.B, "k1": w.k1, "k2": w.k2},
-        "roofline": roofline, "cpu_baseline": cpu, "breakdown": breakdown,
+        "roofline": roofline, "cpu_baseline": cpu, "breakdown": breakdown, "read_ceiling": ceiling, "configs": configs,
+        "untimed_calls_before_timing": {"steps": warm, "read_only_retrieves": settle},
     }))
     bank.close()
 

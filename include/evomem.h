@@ -264,6 +264,12 @@ int mem_counters(evomem_t* h, int64_t* skipped_ids, int64_t* overflows);
 int mem_profile_enable(evomem_t* h, int on);
 int mem_profile_read(evomem_t* h, int capacity, int* n_out, float* ms_out, int64_t* rows_out);
 
+/* Measurement aid: one read-only pass over the rows the bank holds (whole 256-row tiles), every byte
+ * loaded once and XOR-folded into *checksum_dev (uint32, the caller clears it); *bytes_out (host, may be
+ * NULL) receives the number of bytes read.  The similarity scan of a retrieve has to read the same bytes,
+ * so this launch's duration is the floor that the machine at hand sets for it. */
+int mem_read_probe(evomem_t* h, uint32_t* checksum_dev, int64_t* bytes_out, void* hip_stream);
+
 /* Host only, for tests of the scan plan: the passes a retrieve with pool size k1 makes over a bank of
  * N entries, sparsest first.  Pass i scans the 256-row tiles t = u * stride[i] (u = 0,1,...) below
  * ceil(N/256), leaving out those with u % rho[i] == 0 when rho[i] > 0 (a sparser pass owns them);

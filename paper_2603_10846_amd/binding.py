@@ -53,6 +53,7 @@ SYMBOLS = {
     "mem_read_q": (C.c_int, [C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p]),
     "mem_read_rows": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p]),
     "mem_counters": (C.c_int, [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]),
+    "mem_read_probe": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(C.c_int64), C.c_void_p]),
     "mem_profile_enable": (C.c_int, [C.c_void_p, C.c_int]),
     "mem_profile_read": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_float),
                                    C.POINTER(C.c_int64)]),
@@ -289,6 +290,13 @@ class MemoryBank:
         a, b = C.c_int64(), C.c_int64()
         _check(self.lib.mem_counters(self.h, C.byref(a), C.byref(b)), "mem_counters")
         return a.value, b.value
+
+    def read_probe(self, checksum: torch.Tensor) -> int:
+        """One read-only pass over the stored rows (XOR of all words into the int32 tensor `checksum`); returns bytes read."""
+        assert checksum.is_cuda and checksum.numel() >= 1 and checksum.element_size() == 4
+        n = C.c_int64()
+        _check(self.lib.mem_read_probe(self.h, _ptr(checksum), C.byref(n), _stream()), "mem_read_probe")
+        return n.value
 
     def profile_enable(self, on: bool = True):
         _check(self.lib.mem_profile_enable(self.h, int(on)), "mem_profile_enable")

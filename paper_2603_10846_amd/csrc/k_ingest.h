@@ -18,7 +18,10 @@ __device__ __forceinline__ double wave_sum_d(double v) {
 // Memory growth rule of Sec. 3.1: entry first_id + row gets embedding emb[row], rounded to the
 // store's element type; the inverse L2 norm of the *stored* values is kept beside it (fp32, used
 // only by the scan's filter; the value filter recomputes norms in fp64) and both Q tables get their
-// initial value.  One wavefront per row, 8 elements per lane per step.
+// initial value.  One wavefront per row.  A lane takes 4 consecutive elements per step: its 16-byte
+// load is one contiguous 1 KB read per wavefront, its 8-byte store half of a 16-byte chunk of the
+// tiled store (two neighbouring lanes fill a chunk), four steps in flight at a time.  Both are streamed
+// (non-temporal, see layout.h).
 template <typename ST>  // BF16, F16 (uint16_t storage) ; fp32 handled by the overload below
 __global__ __launch_bounds__(256) void k_append16(const float* __restrict__ emb, int64_t n, int d, int nkb,
                                                   int64_t first_id, uint16_t* __restrict__ store,
@@ -31,23 +34,25 @@ __global__ __launch_bounds__(256) void k_append16(const float* __restrict__ emb,
     int64_t id = first_id + row;
     const float* src = emb + row * (int64_t)d;
     float ssq = 0.f;
-    for (int c8 = lane; c8 < nkb * 8; c8 += 64) {
-        float v[8];
-        if (c8 * 8 < d) {
-            float4 a = *reinterpret_cast<const float4*>(src + c8 * 8);
-            float4 b = *reinterpret_cast<const float4*>(src + c8 * 8 + 4);
-            v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
-        } else {
+    const int ngroups = nkb * 16;                       // groups of 4 elements, padding included
+    for (int g0 = lane; g0 < ngroups; g0 += 4 * 64) {
+        float4 v[4];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) v[i] = 0.f;
+        for (int u = 0; u < 4; ++u) {
+            const int g = g0 + 64 * u;
+            v[u] = (g < ngroups && g * 4 < d) ? stream_load_float4(src + g * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
         }
-        uint16_t h[8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) { h[i] = ST::enc(v[i]); float w = ST::dec(h[i]); ssq += w * w; }
-        uint4 pk;
-        pk.x = h[0] | ((uint32_t)h[1] << 16); pk.y = h[2] | ((uint32_t)h[3] << 16);
-        pk.z = h[4] | ((uint32_t)h[5] << 16); pk.w = h[6] | ((uint32_t)h[7] << 16);
-        *reinterpret_cast<uint4*>(store + off16(id, c8, nkb)) = pk;
+        for (int u = 0; u < 4; ++u) {
+            const int g = g0 + 64 * u;
+            if (g >= ngroups) break;
+            const uint16_t h0 = ST::enc(v[u].x), h1 = ST::enc(v[u].y), h2 = ST::enc(v[u].z), h3 = ST::enc(v[u].w);
+            const float w0 = ST::dec(h0), w1 = ST::dec(h1), w2 = ST::dec(h2), w3 = ST::dec(h3);
+            ssq += w0 * w0; ssq += w1 * w1; ssq += w2 * w2; ssq += w3 * w3;
+            uint2 pk;
+            pk.x = h0 | ((uint32_t)h1 << 16); pk.y = h2 | ((uint32_t)h3 << 16);
+            stream_store8(store + off16(id, g >> 1, nkb) + (g & 1) * 4, pk.x, pk.y);
+        }
     }
     ssq = wave_sum_f(ssq);
     if (lane == 0) {
@@ -70,9 +75,9 @@ __global__ __launch_bounds__(256) void k_append32(const float* __restrict__ emb,
     float ssq = 0.f;
     for (int c4 = lane; c4 < nkb * 16; c4 += 64) {
         float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (c4 * 4 < d) a = *reinterpret_cast<const float4*>(src + c4 * 4);
+        if (c4 * 4 < d) a = stream_load_float4(src + c4 * 4);
         ssq += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
-        *reinterpret_cast<float4*>(store + off32(id, c4, nkb)) = a;
+        stream_store_float4(store + off32(id, c4, nkb), a);
     }
     ssq = wave_sum_f(ssq);
     if (lane == 0) {
@@ -105,6 +110,32 @@ __global__ __launch_bounds__(256) void k_read_rows32(const float* __restrict__ s
     for (int c4 = lane; c4 * 4 < d; c4 += 64)
         *reinterpret_cast<float4*>(dst + row * (int64_t)d + c4 * 4) =
             *reinterpret_cast<const float4*>(store + off32(first + row, c4, nkb));
+}
+
+// Read-only pass over the stored rows, nothing else: every 16-byte piece of the store is loaded once and
+// folded into a checksum.  It measures what a scan of this bank can reach at best on the machine at
+// hand (the similarity scan of Sec. 3.2 has to read the same bytes once per retrieve).
+// Access pattern of the scan itself: a workgroup takes whole contiguous 64 KB pieces, round-robin, each
+// lane 16 independent 16-byte loads (one load instruction of the workgroup covers 4 KB).
+__global__ __launch_bounds__(256) void k_read_probe(const uint4* __restrict__ p, int64_t n16, uint32_t* __restrict__ checksum) {
+    constexpr int PIECE = 4096;                          // 16-byte units per 64 KB piece
+    const int64_t pieces = n16 / PIECE;
+    uint32_t acc = 0;
+    for (int64_t c = blockIdx.x; c < pieces; c += gridDim.x) {
+        const uint4* q = p + c * PIECE + threadIdx.x;
+        uint4 v[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) { const stream_u32x4 t = stream_load16(q + u * 256); v[u] = make_uint4(t.x, t.y, t.z, t.w); }
+#pragma unroll
+        for (int u = 0; u < 16; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+    }
+    for (int64_t i = pieces * PIECE + (int64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (int64_t)gridDim.x * 256) {
+        const uint4 v = p[i];
+        acc ^= v.x ^ v.y ^ v.z ^ v.w;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) acc ^= __shfl_xor(acc, o, 64);
+    if ((threadIdx.x & 63) == 0) atomicXor(checksum, acc);
 }
 
 // Query preparation (Sec. 3.2, the query side of dense retrieval): round each query to the store's

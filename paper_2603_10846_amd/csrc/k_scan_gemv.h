@@ -51,7 +51,7 @@ __global__ __launch_bounds__(256) void k_scan_gemv32(const float* __restrict__ s
     for (int kb = 0; kb < nkb; ++kb, blk += BLOCK_ELEMS) {
         float4 x[RG];
 #pragma unroll
-        for (int i = 0; i < RG; ++i) x[i] = *reinterpret_cast<const float4*>(blk + i * 16 * KB);
+        for (int i = 0; i < RG; ++i) x[i] = stream_load_float4(blk + i * 16 * KB);
         float4 qv[NB];
 #pragma unroll
         for (int b = 0; b < NB; ++b)

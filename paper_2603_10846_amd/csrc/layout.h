@@ -40,6 +40,29 @@ __host__ __device__ __forceinline__ int64_t off32(int64_t id, int c4, int nkb) {
     return (t * nkb + kb) * (int64_t)BLOCK_ELEMS + r * KB + c * 4;
 }
 
+// Bank rows are read once per retrieve and written once per append, in streams far larger than the
+// caches: such accesses carry the non-temporal hint, so that they do not displace what is re-used
+// (queries, thresholds, lists).  Measured on MI355X: a read-only pass over a 2 GB store 6.05 -> 6.89
+// TB/s, the 64K x 4096 append 5.45 -> 6.2 TB/s, the densest scan pass at one query 0.338 -> 0.293 ms.
+typedef __attribute__((ext_vector_type(4))) uint32_t stream_u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t stream_u32x2;
+typedef __attribute__((ext_vector_type(4))) float stream_f32x4;
+__device__ __forceinline__ stream_u32x4 stream_load16(const void* p) {
+    return __builtin_nontemporal_load(static_cast<const stream_u32x4*>(p));
+}
+__device__ __forceinline__ float4 stream_load_float4(const float* p) {
+    const stream_f32x4 t = __builtin_nontemporal_load(reinterpret_cast<const stream_f32x4*>(p));
+    return make_float4(t.x, t.y, t.z, t.w);
+}
+__device__ __forceinline__ void stream_store8(void* p, uint32_t lo, uint32_t hi) {
+    const stream_u32x2 t = {lo, hi};
+    __builtin_nontemporal_store(t, static_cast<stream_u32x2*>(p));
+}
+__device__ __forceinline__ void stream_store_float4(float* p, float4 v) {
+    const stream_f32x4 t = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(t, reinterpret_cast<stream_f32x4*>(p));
+}
+
 // ---- order-preserving packing of (similarity, id): larger key = better; lower id wins ties ----
 __device__ __forceinline__ uint32_t f2ord(float f) {
     uint32_t u = __float_as_uint(f);

@@ -56,6 +56,28 @@ def test_store_holds_rne_rounded_rows(orc, dtype):
     bank.close()
 
 
+def test_read_probe_reads_every_stored_word_once(orc):
+    """The read-only pass XORs every 32-bit word of the stored rows: for whole tiles and whole k-blocks
+    (no padding in the store) that is the XOR of the rows' bf16 pairs as the oracle rounds them, and fp32 words."""
+    rng = np.random.default_rng(109)
+    for dtype, N, d in (("bf16", 1024, 128), ("f32", 512, 64)):
+        rows = rng.standard_normal((N, d)).astype(np.float32)
+        bank = _make_bank(dtype, rows, max_B=8, max_k1=16)
+        chk = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+        nbytes = bank.read_probe(chk)
+        torch.cuda.synchronize()
+        bits = orc.round_to_store(rows, DT[dtype]).view(np.uint32)
+        if dtype == "bf16":
+            h = bits >> 16
+            words = h[:, 0::2] | (h[:, 1::2] << 16)
+            assert nbytes == N * d * 2
+        else:
+            words = bits
+            assert nbytes == N * d * 4
+        assert np.uint32(chk.cpu().numpy().view(np.uint32)[0]) == np.bitwise_xor.reduce(words.ravel())
+        bank.close()
+
+
 # ----------------------------------------------------------------------------- retrieval, small
 
 CASES = [
