@@ -108,6 +108,18 @@ int mem_retrieve(evomem_t* h, const float* queries_dev, int B, int stage, int k1
                  int32_t* out_cand_ids_dev, float* out_cand_sims_dev, void* hip_stream);
 
 /*
+ * Per-query status of the latest retrieve call of any kind on this handle (enqueued on the same stream,
+ * or ordered after it): copies B words to out_flags_dev (uint32[B]) on the stream, without synchronising.
+ * Bit 0 (MEM_FLAG_OVERFLOW): during some scan pass more than 8192 rows of the bank reached the query's
+ * running threshold (the k1-th best similarity seen so far, minus a rounding margin) -- a mass of
+ * near-duplicates of the pool's last members.  The rows beyond 8192 were not kept, so the pool of such a
+ * query may miss members whose similarity ties with its last ones; every other query of the call is
+ * exact.  Errors: MEM_EINVAL, MEM_ESTATE (no retrieve yet, or B larger than that call's), MEM_EHIP.
+ */
+#define MEM_FLAG_OVERFLOW 1u
+int mem_retrieve_flags(evomem_t* h, uint32_t* out_flags_dev, int B, void* hip_stream);
+
+/*
  * mem_retrieve for callers that cannot allocate device memory (code under HIP graph capture, tight
  * serving loops, harnesses that forbid hipMalloc) and so cannot size and bring a workspace of their
  * own: the same call, same arguments, same results bit for bit, but every intermediate result lives
@@ -119,7 +131,7 @@ int mem_retrieve(evomem_t* h, const float* queries_dev, int B, int stage, int k1
  * looks the array's address up and enqueues a small kernel that clears its counter block.
  * All handles and streams of a process share the one array of a GPU: calls that overlap on one GPU
  * race; calls ordered on one stream (or otherwise serialised) do not.  Queries whose survivor list
- * overflows are counted inside the array, not in the handle's mem_counters.
+ * overflows are counted inside the array, not in the handle's mem_counters (mem_retrieve_flags reports them).
  */
 int mem_retrieve_static(evomem_t* h, const float* queries_dev, int B, int stage, int k1, int k2,
                         float lambda, int32_t* out_ids_dev, float* out_scores_dev,
@@ -251,8 +263,8 @@ int mem_restore(evomem_t* h, int64_t n);
 int mem_read_rows(evomem_t* h, int64_t first, int64_t n, float* dst_dev, void* hip_stream);
 
 /* Synchronises the device.  *skipped_ids: ids outside the bank that mem_update_q and mem_select_by_q
- * have skipped so far; *overflows: queries
- * whose survivor list overflowed during some retrieve (their pool may then be inexact). */
+ * have skipped so far; *overflows: queries whose survivor list overflowed during some retrieve so far
+ * (their pool may then be inexact; mem_retrieve_flags names them per call, without synchronising). */
 int mem_counters(evomem_t* h, int64_t* skipped_ids, int64_t* overflows);
 
 /* Per-kernel timing with HIP events on the call's stream (off by default).  While on, every

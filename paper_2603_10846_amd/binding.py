@@ -34,6 +34,7 @@ SYMBOLS = {
                                C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "mem_retrieve_static": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_float,
                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "mem_retrieve_flags": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p]),
     "mem_retrieve_eps": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_float, C.c_float,
                                    C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                    C.c_void_p]),
@@ -170,6 +171,12 @@ class MemoryBank:
         _check(self.lib.mem_retrieve(self.h, _ptr(queries), B, stage, k1, k2, lam, _ptr(ids), _ptr(scores),
                                      _ptr(cid), _ptr(csim), _stream()), "mem_retrieve")
         return ids, scores, cid, csim
+
+    def retrieve_flags(self, B: int) -> torch.Tensor:
+        """Status words (int32[B]) of the latest retrieve: bit 0 = a survivor list of that query overflowed."""
+        out = torch.empty(B, dtype=torch.int32, device=self.device)
+        _check(self.lib.mem_retrieve_flags(self.h, _ptr(out), B, _stream()), "mem_retrieve_flags")
+        return out
 
     def retrieve_static(self, queries: torch.Tensor, stage: int, k1: int, k2: int, lam: float, out):
         """mem_retrieve with the library's built-in scratch array; `out` = (ids, scores, cand_ids or None,

@@ -31,20 +31,20 @@ constexpr int GEMV_MAX_B = 4;       // fp32 stores: at most this many queries us
 constexpr int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
 struct Workspace {   // byte offsets into a scratch area (the caller's workspace, or the library's own array)
-    size_t counters, qf, qop, invq, invq64, thr, cnt, surv, exact, total;
+    size_t counters, qf, qop, invq, invq64, thr, cnt, flags, surv, exact, total;
 };
 
 // A retrieve pads its batch to a multiple of its query tile (32 .. 256 queries), so the per-query
 // arrays are sized for max_B rounded up to `bpad` (256 covers every tile).
 constexpr Workspace carve(int d, int dtype, int max_B, int max_k1, int bpad = 256) {
     const int64_t dpad = round_up(d, KB), Bp = round_up(max_B, bpad);
-    const size_t sizes[9] = {256, (size_t)Bp * dpad * 4,
-                             (size_t)Bp * (dpad + KB) * (dtype == MEM_F32 ? 4 : 2),   // + one all-zero k-block
-                             (size_t)Bp * 4, (size_t)Bp * 8, (size_t)Bp * 4, (size_t)Bp * 4,
-                             (size_t)Bp * SURV_CAP * 8, (size_t)Bp * keep_of(max_k1) * 8};
-    size_t at[10] = {};
-    for (int i = 0; i < 9; ++i) at[i + 1] = (size_t)round_up((int64_t)(at[i] + sizes[i]), 256);
-    return Workspace{at[0], at[1], at[2], at[3], at[4], at[5], at[6], at[7], at[8], at[9]};
+    const size_t sizes[10] = {256, (size_t)Bp * dpad * 4,
+                              (size_t)Bp * (dpad + KB) * (dtype == MEM_F32 ? 4 : 2),   // + one all-zero k-block
+                              (size_t)Bp * 4, (size_t)Bp * 8, (size_t)Bp * 4, (size_t)Bp * 4, (size_t)Bp * 4,
+                              (size_t)Bp * SURV_CAP * 8, (size_t)Bp * keep_of(max_k1) * 8};
+    size_t at[11] = {};
+    for (int i = 0; i < 10; ++i) at[i + 1] = (size_t)round_up((int64_t)(at[i] + sizes[i]), 256);
+    return Workspace{at[0], at[1], at[2], at[3], at[4], at[5], at[6], at[7], at[8], at[9], at[10]};
 }
 
 // Where a retrieve keeps its intermediate results.
@@ -81,6 +81,8 @@ struct evomem {
     bool prof_on;
     int prof_n;
     uint32_t* tags = nullptr;   // per-entry tags of typed / masked retrieval (caller's buffer), or null
+    const uint32_t* last_flags = nullptr;   // per-query status words of the latest retrieve (in the scratch it used)
+    int last_B = 0;
     std::vector<hipEvent_t> ev;
     std::vector<int64_t> prof_rows;
 };
@@ -436,9 +438,12 @@ static int retrieve_impl(evomem_t* h, const float* queries_dev, int B, int stage
     double* invq64 = (double*)(ws + sc.w.invq64);
     float* thr = (float*)(ws + sc.w.thr);
     uint32_t* cnt = (uint32_t*)(ws + sc.w.cnt);
+    uint32_t* flags = (uint32_t*)(ws + sc.w.flags);
     uint64_t* surv = (uint64_t*)(ws + sc.w.surv);
     double* exact = (double*)(ws + sc.w.exact);
     const int exact_stride = sc.exact_stride;
+    h->last_flags = flags;
+    h->last_B = B;
     uint32_t* counters = (uint32_t*)(ws + sc.w.counters);
 
     Plan plan{};
@@ -451,11 +456,11 @@ static int retrieve_impl(evomem_t* h, const float* queries_dev, int B, int stage
         cnt0 = (uint32_t)((int64_t)(L0.ntiles - 1) * TILE_ROWS + in_last);
     }
     if (h->dtype == MEM_F32)
-        hipLaunchKernelGGL(k_prep_queries<0>, dim3(Bp), dim3(256), 0, st, queries_dev, B, Bp, h->d, h->nkb, qf, qop, invq, invq64, thr, cnt, cnt0);
+        hipLaunchKernelGGL(k_prep_queries<0>, dim3(Bp), dim3(256), 0, st, queries_dev, B, Bp, h->d, h->nkb, qf, qop, invq, invq64, thr, cnt, flags, cnt0);
     else if (h->dtype == MEM_BF16)
-        hipLaunchKernelGGL(k_prep_queries<1>, dim3(Bp), dim3(256), 0, st, queries_dev, B, Bp, h->d, h->nkb, qf, qop, invq, invq64, thr, cnt, cnt0);
+        hipLaunchKernelGGL(k_prep_queries<1>, dim3(Bp), dim3(256), 0, st, queries_dev, B, Bp, h->d, h->nkb, qf, qop, invq, invq64, thr, cnt, flags, cnt0);
     else
-        hipLaunchKernelGGL(k_prep_queries<2>, dim3(Bp), dim3(256), 0, st, queries_dev, B, Bp, h->d, h->nkb, qf, qop, invq, invq64, thr, cnt, cnt0);
+        hipLaunchKernelGGL(k_prep_queries<2>, dim3(Bp), dim3(256), 0, st, queries_dev, B, Bp, h->d, h->nkb, qf, qop, invq, invq64, thr, cnt, flags, cnt0);
     LAUNCHCHK();
 
     // rounding margin of the scan's fp32 similarities
@@ -489,14 +494,25 @@ static int retrieve_impl(evomem_t* h, const float* queries_dev, int B, int stage
                 int64_t rows = (int64_t)L.ntiles * TILE_ROWS;
                 h->prof_rows[h->prof_n++] = rows;
             }
-            if (fused_tail && li == plan.n - 1) break;          // the last selection runs inside the fused kernel below
-            hipLaunchKernelGGL(k_select, dim3(B), dim3(1024), 0, st, surv, cnt, thr, (const float*)invq, counters, k1, margin, mask.tags != nullptr, keep_of(k1));
+            if (li == plan.n - 1) {
+                if (fused_tail) break;                              // the last selection runs inside the fused kernel below
+                // the last selection refines a crowded band with exactly accumulated similarities
+#define EVK_SELF(DT) hipLaunchKernelGGL(k_select_final<DT>, dim3(B), dim3(1024), 0, st, surv, cnt, thr, (const float*)invq, counters, flags, k1, \
+                margin, mask.tags != nullptr, keep_of(k1), (const void*)h->store, (const float*)qf, (const double*)invq64, h->nkb)
+                if (h->dtype == MEM_F32) EVK_SELF(0);
+                else if (h->dtype == MEM_BF16) EVK_SELF(1);
+                else EVK_SELF(2);
+#undef EVK_SELF
+            } else {
+                hipLaunchKernelGGL(k_select, dim3(B), dim3(1024), 0, st, surv, cnt, thr, (const float*)invq, counters, flags, k1, margin,
+                                   mask.tags != nullptr, keep_of(k1));
+            }
             LAUNCHCHK();
         }
         if (fused_tail) {
             const float* qs = (const float*)(h->q + (int64_t)stage * h->capacity);
 #define EVK_TAIL(DT) hipLaunchKernelGGL(k_select_rescore_rerank<DT>, dim3(B), dim3(1024), 0, st, surv, cnt, thr, (const float*)invq, counters, \
-                k1, margin, mask.tags != nullptr, keep_of(k1), (const void*)h->store, (const float*)qf, (const double*)invq64, exact, h->nkb,      \
+                flags, k1, margin, mask.tags != nullptr, keep_of(k1), (const void*)h->store, (const float*)qf, (const double*)invq64, exact, h->nkb,      \
                 exact_stride, qs, k2, (double)lambda, out_ids_dev, out_scores_dev, out_cand_ids_dev, out_cand_sims_dev, eg)
             if (h->dtype == MEM_F32) EVK_TAIL(0);
             else if (h->dtype == MEM_BF16) EVK_TAIL(1);
@@ -585,6 +601,15 @@ extern "C" int mem_retrieve_static(evomem_t* h, const float* queries_dev, int B,
     return retrieve_impl(h, queries_dev, B, stage, k1, k2, lambda, out_ids_dev, out_scores_dev, out_cand_ids_dev,
                          out_cand_sims_dev, hip_stream, greedy, Mask{nullptr, nullptr, nullptr},
                          Scratch{scratch_ptr[cur], STATIC_W, keep_of(STATIC_MAX_K1)}, STATIC_MAX_B, STATIC_MAX_K1);
+}
+
+extern "C" int mem_retrieve_flags(evomem_t* h, uint32_t* out_flags_dev, int B, void* hip_stream) {
+    if (!h || B < 0 || (B > 0 && !out_flags_dev)) return MEM_EINVAL;
+    if (B == 0) return MEM_OK;
+    if (!h->last_flags || B > h->last_B) return MEM_ESTATE;      // no retrieve yet, or a smaller one
+    HIPCHK(hipMemcpyAsync(out_flags_dev, h->last_flags, sizeof(uint32_t) * (size_t)B, hipMemcpyDeviceToDevice,
+                          static_cast<hipStream_t>(hip_stream)));
+    return MEM_OK;
 }
 
 extern "C" int mem_retrieve_eps(evomem_t* h, const float* queries_dev, int B, int stage, int k1, int k2, float lambda,

@@ -153,7 +153,7 @@ __global__ __launch_bounds__(256) void k_prep_queries(const float* __restrict__ 
                                                       float* __restrict__ qf, uint16_t* __restrict__ qop,
                                                       float* __restrict__ invq, double* __restrict__ invq64,
                                                       float* __restrict__ thr, uint32_t* __restrict__ cnt,
-                                                      uint32_t cnt0) {
+                                                      uint32_t* __restrict__ flags, uint32_t cnt0) {
     int b = blockIdx.x, tid = threadIdx.x;
     int dpad = nkb * KB;
     __shared__ double red[256];
@@ -215,6 +215,7 @@ __global__ __launch_bounds__(256) void k_prep_queries(const float* __restrict__ 
         // can never reach.  Finite values keep the scan's arithmetic free of inf - inf.
         thr[b] = live ? (float)(-2.0 / inv) : 1.0f;
         cnt[b] = live ? cnt0 : 0u;     // rows the sparsest pass will write without counting
+        flags[b] = 0u;                 // per-query status of this retrieve (bit 0: a survivor list overflowed)
     }
 }
 

@@ -1,5 +1,7 @@
 // Selection kernels: survivor lists -> candidate pool -> value filter (Sec. 3.2).
 #pragma once
+#include <type_traits>
+
 #include "k_ingest.h"
 #include "layout.h"
 
@@ -51,9 +53,19 @@ __device__ __forceinline__ uint32_t wave_or_u32(uint32_t x) {
 // Keys live in registers (8 per lane, 1024 lanes); the passes start at the highest bit on which two
 // keys differ; each builds per-wavefront digit histograms in LDS, sums them, and one wavefront
 // picks the digit by a suffix scan.
-__device__ __forceinline__ void select_one_query(const int b, uint64_t* surv, uint32_t* cnt,
-                                                 float* thr, const float* invq,
-                                                 uint32_t* counters, int k1, float margin, int may_have_empty, int keep_max) {
+// A list that overflowed during the pass (more than SURV_CAP rows reached the threshold; the surplus was
+// dropped) is counted and the query is flagged: its pool may then miss members.
+// More than keep_max keys inside the margin ("crowded band"; near-duplicate entries do that):
+//   SEL_PASS   (between scan passes) every key of the band is kept -- any of them may belong to the pool;
+//   SEL_FINAL  (after the last pass) likewise, and the function returns true: the caller replaces the
+//              keys' similarities by exactly accumulated ones (rescore_one_query<DT, true>) and selects
+//              again with a margin of two fp32 roundings;
+//   SEL_EXACT  (that second selection) a band that is still crowded can only be one of ties within
+//              fp32 resolution: the k1 best keys are kept, lower ids first among equal similarities.
+enum { SEL_PASS = 0, SEL_FINAL = 1, SEL_EXACT = 2 };
+__device__ __forceinline__ bool select_one_query(const int b, uint64_t* surv, uint32_t* cnt,
+                                                 float* thr, const float* invq, uint32_t* counters, uint32_t* flags,
+                                                 int k1, float margin, int may_have_empty, int keep_max, int mode) {
     __shared__ uint32_t hist[16][256];
     __shared__ uint32_t tot[256];
     __shared__ uint64_t pivot_s, or_s[16];
@@ -62,10 +74,10 @@ __device__ __forceinline__ void select_one_query(const int b, uint64_t* surv, ui
     uint64_t* list = surv + (int64_t)b * SURV_CAP;
     const uint32_t raw = cnt[b];
     const int n = raw > (uint32_t)SURV_CAP ? SURV_CAP : (int)raw;
-    if (raw > (uint32_t)SURV_CAP && tid == 0) atomicAdd(counters + 1, 1u);
+    if (raw > (uint32_t)SURV_CAP && tid == 0) { atomicAdd(counters + 1, 1u); flags[b] |= 1u; }
     if (!may_have_empty && n < k1) {    // fewer rows than the pool size: keep them all, no threshold
         if (tid == 0) { cnt[b] = (uint32_t)n; thr[b] = -2.0f / invq[b]; }   // finite floor, see k_prep_queries
-        return;
+        return false;
     }
     uint64_t key[8];
 #pragma unroll
@@ -89,7 +101,7 @@ __device__ __forceinline__ void select_one_query(const int b, uint64_t* surv, ui
                 if (key[i] != 0) list[atomicAdd(&nout_s, 1u)] = key[i];
             __syncthreads();
             if (tid == 0) { cnt[b] = nout_s; thr[b] = -2.0f / invq[b]; }
-            return;
+            return false;
         }
         __syncthreads();
         if (tid == 0) band_s = 0;
@@ -162,27 +174,32 @@ __device__ __forceinline__ void select_one_query(const int b, uint64_t* surv, ui
     for (int o = 32; o > 0; o >>= 1) mine += __shfl_xor(mine, o, 64);
     if (lane == 0 && mine) atomicAdd(&band_s, mine);
     __syncthreads();
-    if (band_s > (uint32_t)keep_max) cutkey = pivot;    // band too crowded: keep exactly the k1 best
+    const bool crowded = band_s > (uint32_t)keep_max;   // uniform
+    if (crowded && mode == SEL_EXACT) cutkey = pivot;   // ties within fp32 resolution: exactly the k1 best
 #pragma unroll
     for (int i = 0; i < 8; ++i)
         if (key[i] != 0 && key[i] >= cutkey) list[atomicAdd(&nout_s, 1u)] = key[i];
     __syncthreads();
     if (tid == 0) { cnt[b] = nout_s; thr[b] = tau / invq[b]; }
+    return crowded && mode == SEL_FINAL;
 }
 
 __global__ __launch_bounds__(1024) void k_select(uint64_t* __restrict__ surv, uint32_t* __restrict__ cnt,
                                                  float* __restrict__ thr, const float* __restrict__ invq,
-                                                 uint32_t* __restrict__ counters, int k1, float margin, int may_have_empty, int keep_max) {
-    select_one_query((int)blockIdx.x, surv, cnt, thr, invq, counters, k1, margin, may_have_empty, keep_max);
+                                                 uint32_t* __restrict__ counters, uint32_t* __restrict__ flags, int k1, float margin,
+                                                 int may_have_empty, int keep_max) {
+    select_one_query((int)blockIdx.x, surv, cnt, thr, invq, counters, flags, k1, margin, may_have_empty, keep_max, SEL_PASS);
 }
 
 // Exact similarities of the selected candidates: one wavefront per (query, candidate) re-reads the
 // stored row and accumulates dot product and squared norm in fp64 (products of 16-bit values are
 // exact, so this is the cosine of the stored vectors up to fp64 rounding).
-template <int DT>
+// REQUANT: instead of storing the fp64 similarity, the candidate's key is rewritten with it (rounded to
+// fp32: resolution 6e-8), for a second selection over a crowded band.
+template <int DT, bool REQUANT = false>
 __device__ __forceinline__ void rescore_one_query(const int b, const int part, const int parts,
                                                   const void* store_, const float* qf,
-                                                  const double* invq64, const uint64_t* surv,
+                                                  const double* invq64, std::conditional_t<REQUANT, uint64_t, const uint64_t>* surv,
                                                   const uint32_t* cnt, double* exact,
                                                   int nkb, int exact_stride) {
     // One workgroup per query; 16 lanes per candidate row, so a wavefront works on four rows at a
@@ -235,8 +252,39 @@ __device__ __forceinline__ void rescore_one_query(const int b, const int part, c
         }
 #pragma unroll
         for (int o = 8; o > 0; o >>= 1) { dot += __shfl_xor(dot, o, 64); ssq += __shfl_xor(ssq, o, 64); }
-        if (live && sub == 0) exact[(int64_t)b * exact_stride + j] = dot * invq64[b] * (1.0 / sqrt(ssq));
+        if (live && sub == 0) {
+            const double sim = dot * invq64[b] * (1.0 / sqrt(ssq));
+            if constexpr (REQUANT) surv[(int64_t)b * SURV_CAP + j] = pack_key(sim == sim ? (float)sim : -INFINITY, id);
+            else exact[(int64_t)b * exact_stride + j] = sim;
+        }
     }
+}
+
+// The selection after the last scan pass, with the refinement of a crowded band (see select_one_query).
+constexpr float EXACT_KEY_MARGIN = 2.4e-7f;     // two fp32 roundings of a similarity of magnitude <= 1
+template <int DT>
+__device__ __forceinline__ void select_final_one_query(const int b, uint64_t* surv, uint32_t* cnt, float* thr,
+                                                       const float* invq, uint32_t* counters, uint32_t* flags, int k1,
+                                                       float margin, int may_have_empty, int keep_max,
+                                                       const void* store_, const float* qf, const double* invq64, int nkb) {
+    const bool crowded = select_one_query(b, surv, cnt, thr, invq, counters, flags, k1, margin, may_have_empty, keep_max, SEL_FINAL);
+    __syncthreads();
+    if (crowded) {                                  // uniform
+        rescore_one_query<DT, true>(b, 0, 1, store_, qf, invq64, surv, cnt, nullptr, nkb, 0);
+        __syncthreads();
+        select_one_query(b, surv, cnt, thr, invq, counters, flags, k1, EXACT_KEY_MARGIN, may_have_empty, keep_max, SEL_EXACT);
+        __syncthreads();
+    }
+}
+
+template <int DT>
+__global__ __launch_bounds__(1024) void k_select_final(uint64_t* __restrict__ surv, uint32_t* __restrict__ cnt, float* __restrict__ thr,
+                                                       const float* __restrict__ invq, uint32_t* __restrict__ counters,
+                                                       uint32_t* __restrict__ flags, int k1, float margin, int may_have_empty,
+                                                       int keep_max, const void* __restrict__ store_, const float* __restrict__ qf,
+                                                       const double* __restrict__ invq64, int nkb) {
+    select_final_one_query<DT>((int)blockIdx.x, surv, cnt, thr, invq, counters, flags, k1, margin, may_have_empty, keep_max,
+                               store_, qf, invq64, nkb);
 }
 
 template <int DT>
@@ -443,14 +491,13 @@ __global__ __launch_bounds__(RERANK_T) void k_rerank(const uint64_t* __restrict_
 template <int DT>
 __global__ __launch_bounds__(1024) void k_select_rescore_rerank(
         uint64_t* __restrict__ surv, uint32_t* __restrict__ cnt, float* __restrict__ thr, const float* __restrict__ invq,
-        uint32_t* __restrict__ counters, int k1, float margin, int may_have_empty, int keep_max,
+        uint32_t* __restrict__ counters, uint32_t* __restrict__ flags, int k1, float margin, int may_have_empty, int keep_max,
         const void* __restrict__ store_, const float* __restrict__ qf, const double* __restrict__ invq64,
         double* __restrict__ exact, int nkb, int exact_stride,
         const float* __restrict__ qstage, int k2, double lambda, int32_t* __restrict__ out_ids, float* __restrict__ out_scores,
         int32_t* __restrict__ cand_ids, float* __restrict__ cand_sims, EpsGreedy eg) {
     const int b = (int)blockIdx.x;
-    select_one_query(b, surv, cnt, thr, invq, counters, k1, margin, may_have_empty, keep_max);
-    __syncthreads();
+    select_final_one_query<DT>(b, surv, cnt, thr, invq, counters, flags, k1, margin, may_have_empty, keep_max, store_, qf, invq64, nkb);
     rescore_one_query<DT>(b, 0, 1, store_, qf, invq64, surv, cnt, exact, nkb, exact_stride);
     __syncthreads();
     rerank_one_query<1024>(b, surv, cnt, exact, qstage, k1, k2, lambda, out_ids, out_scores, cand_ids, cand_sims, eg, exact_stride);

@@ -336,6 +336,7 @@ def test_survivor_list_overflow_is_counted(orc):
     bank = _make_bank("bf16", rows, max_B=8, max_k1=64)
     q = np.concatenate([v, _unit(rng, 5, 128)])
     out = parity.gpu_retrieve(bank, torch, q, 0, 64, 8, 0.0)
+    flags = bank.retrieve_flags(len(q)).cpu().numpy()          # per call and per query, no device-wide wait
     skipped, overflows = bank.counters()
     assert skipped == 0 and overflows >= 1
     pool = out["cand_ids"][0]
@@ -350,11 +351,47 @@ def test_survivor_list_overflow_is_counted(orc):
     assert crowded[0] and overflows >= 1
     safe = [b for b in range(len(q)) if not crowded[b]]
     assert len(safe) >= 3
+    assert flags[0] & 1 and all(flags[b] == 0 for b in safe)
     parity.check_retrieve(orc, st, qr, np.zeros(len(rows), np.float32), 64, 8, 0.0, out, sample=safe)
     before = bank.counters()[1]
     out2 = parity.gpu_retrieve(bank, torch, q[safe], 0, 64, 8, 0.0)
     parity.check_retrieve(orc, st, qr[safe], np.zeros(len(rows), np.float32), 64, 8, 0.0, out2)
-    assert bank.counters()[1] == before
+    assert bank.counters()[1] == before and not bank.retrieve_flags(len(safe)).cpu().numpy().any()
+    bank.close()
+
+
+@pytest.mark.parametrize("dtype,nq,k1", [("bf16", 5, 64), ("bf16", 130, 100), ("f32", 2, 32), ("f16", 40, 200)])
+def test_crowded_band_of_distinct_near_ties(orc, dtype, nq, k1):
+    """Thousands of entries whose similarities to a query differ by less than the scan's rounding margin
+    (successive refinements of one kernel give such near-duplicates): far more than the 512 candidates that
+    are re-scored at once.  The pool must still be the oracle's up to the resolution of an fp32 similarity:
+    no list overflows, and whatever differs from the oracle's pool lies within 3e-7 of its last member."""
+    rng = np.random.default_rng([13, nq, k1])
+    d, n_near, n_far = 128, 3000, 9000
+    v = _unit(rng, 1, d)
+    near = v + np.float32(0.001) * rng.standard_normal((n_near, d)).astype(np.float32) * rng.uniform(0, 1, (n_near, 1)).astype(np.float32)
+    rows = np.concatenate([near / np.linalg.norm(near, axis=1, keepdims=True), _unit(rng, n_far, d)]).astype(np.float32)
+    rows = rows[rng.permutation(len(rows))]
+    q = _unit(rng, nq, d)
+    q[0] = v[0]
+    if nq > 3:
+        q[3] = (v[0] + np.float32(0.001) * rng.standard_normal(d)).astype(np.float32)
+    qtab = rng.uniform(-1, 1, (2, len(rows))).astype(np.float32)
+    print(f"crowded band {dtype} B={nq} k1={k1}", flush=True)
+    bank = _make_bank(dtype, rows, qtab, max_B=max(nq, 8), max_k1=256)
+    gpu = parity.gpu_retrieve(bank, torch, q, 1, k1, 8, 0.5)
+    assert not bank.retrieve_flags(nq).cpu().numpy().any() and bank.counters() == (0, 0)
+    st, qr = orc.round_to_store(rows, DT[dtype]), orc.round_to_store(q, DT[dtype])
+    o_ids, o_sims = orc.recall(st, qr, k1, threads=8)
+    in_band = ((o_sims[0, k1 - 1] - orc.sims_of(st, qr[0], np.arange(len(rows), dtype=np.int32))) < 2e-5).sum()
+    assert in_band > 600                                        # the case is what it claims to be
+    for b in range(nq):
+        only_gpu = sorted(set(gpu["cand_ids"][b].tolist()) - set(o_ids[b].tolist()))
+        if only_gpu:
+            s_ = orc.sims_of(st, qr[b], np.array(only_gpu, np.int32))
+            assert np.all(s_ > o_sims[b, k1 - 1] - 3e-7), (b, only_gpu, s_, o_sims[b, k1 - 1])
+    stats = parity.check_retrieve(orc, st, qr, qtab[1], k1, 8, 0.5, gpu, ora_recall=(o_ids, o_sims))
+    print("crowded band stats", stats, flush=True)
     bank.close()
 
 
