@@ -16,12 +16,15 @@ import numpy as np
 F32, BF16, F16 = 0, 1, 2
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "evomem_oracle.c")
-_LIB = os.path.join(_HERE, "libevomem_oracle.so")
+# EVOMEM_ORACLE_LIB selects another build of the same source (the sanitizer build of the CPU tests)
+_LIB = os.environ.get("EVOMEM_ORACLE_LIB") or os.path.join(_HERE, "libevomem_oracle.so")
 _lib = None
 
 
 def build(force: bool = False) -> str:
     """Compile the C oracle with gcc (-O2, contraction off, OpenMP over queries)."""
+    if os.environ.get("EVOMEM_ORACLE_LIB"):
+        return _LIB                                   # built by whoever named it
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         subprocess.check_call(
             ["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared",
