@@ -341,6 +341,7 @@ def main():
     achieved = alg_bytes / (avg_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": ("k_scan_gemv32" if w.B <= 4 and w.dtype == "f32" else "k_scan_mfma") + " (densest pass)", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None if args.batch else measured_traffic(args.workload),
+                "traffic_source": "recorded counters (profiles/k_scan_mfma_clustered_hbm_counters.txt), not measured in this run",
                 "avg_launch_ms": round(avg_ms, 4), "launches": len(dense), "rows_per_launch": int(dense_rows),
                 "bytes_per_row": w.d * elem, "algorithmic_bytes_per_launch": int(alg_bytes),
                 "mfma_tflops": round(2.0 * w.B * dense_rows * w.d / (avg_ms * 1e-3) / 1e12, 1),

@@ -17,7 +17,9 @@
  *     data_ptr) and must stay valid until mem_destroy.  The library owns only its host handle and
  *     a few HIP events.  Pointers without the suffix are HOST memory.
  *   - `hip_stream` is a hipStream_t passed as void*; NULL is the default stream.  Calls on one
- *     stream are ordered; using one handle from several streams at once is not supported.
+ *     stream are ordered; using one handle from several streams at once is not supported, and the
+ *     library's calls must come from one host thread at a time (it keeps small per-device caches,
+ *     such as how many workgroups of a kernel the device holds, without locks).
  *   - No call synchronises with the host except those documented to do so.
  *   - Entry ids are dense int32: 0,1,2,... in append order, never reused (the bank only grows).
  *   - Similarity is the cosine between the STORED vectors: rows and queries are rounded to the
