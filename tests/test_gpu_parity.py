@@ -152,9 +152,16 @@ def test_edge_cases(orc):
     rows = _unit(rng, 10, 64)
     q = _unit(rng, 3, 64)
     bank = B.MemoryBank(64, "f16", 300, max_B=8, max_k1=64)
+    with pytest.raises(B.MemError) as e:                             # no retrieve yet: no status words to report
+        bank.retrieve_flags(1)
+    assert e.value.status == B.MEM_ESTATE
     # empty bank: everything padded
     out = parity.gpu_retrieve(bank, torch, q, 0, 16, 4, 0.5)
     assert np.all(out["ids"] == -1) and np.all(np.isneginf(out["scores"])) and np.all(out["cand_ids"] == -1)
+    assert bank.retrieve_flags(3).cpu().numpy().tolist() == [0, 0, 0] and bank.retrieve_flags(0).numel() == 0
+    with pytest.raises(B.MemError) as e:                             # more queries than that call had
+        bank.retrieve_flags(4)
+    assert e.value.status == B.MEM_ESTATE
     # one entry: pool of one, z-scores are 0
     bank.append(_dev(rows[:1]))
     out = parity.gpu_retrieve(bank, torch, q, 0, 16, 4, 0.5)
