@@ -721,6 +721,37 @@ def _check_masked(orc, bank, dtype, rows, q, tags, allow, exclude, qtab, stage, 
     return total
 
 
+def test_masked_retrieval_with_a_crowded_band(orc):
+    """Typed retrieval over a bank with thousands of near-duplicates of one row: the accepted half of them
+    crowds the band after the last pass (the refinement of the selection also runs with empty list slots),
+    eps-greedy selection on the same bank stays consistent with the greedy pool."""
+    rng = np.random.default_rng(131)
+    d, n_near, n_far = 128, 2600, 6000
+    v = _unit(rng, 1, d)
+    near = v + np.float32(0.001) * rng.standard_normal((n_near, d)).astype(np.float32) * rng.uniform(0, 1, (n_near, 1)).astype(np.float32)
+    rows = np.concatenate([near / np.linalg.norm(near, axis=1, keepdims=True), _unit(rng, n_far, d)]).astype(np.float32)
+    rows = rows[rng.permutation(len(rows))]
+    N = len(rows)
+    tags = (rng.integers(0, 2, N) | (rng.integers(0, 50, N) << 8)).astype(np.uint32)      # two types, 50 groups
+    qtab = rng.uniform(-1, 1, (2, N)).astype(np.float32)
+    q = _unit(rng, 6, d)
+    q[0] = v[0]
+    q[5] = v[0]
+    allow = np.array([1, 3, 2, 1, 3, 2], np.uint32)
+    exclude = np.array([0xffffffff, 7, 0xffffffff, 3, 0xffffffff, 11], np.uint32)
+    bank = _make_bank("bf16", rows, qtab, max_B=8, max_k1=256)
+    bank.set_tags(0, torch.from_numpy(tags.astype(np.int64)))
+    total = _check_masked(orc, bank, "bf16", rows, q, tags, allow, exclude, qtab, 0, 64, 8, 0.5)
+    assert total["queries"] == 6 and not bank.retrieve_flags(6).cpu().numpy().any()
+    # eps-greedy on the crowded, unmasked bank: eps = 0 equals the greedy call bit for bit
+    a = bank.retrieve(_dev(q), 0, 64, 8, 0.5, want_candidates=True)
+    b_ = bank.retrieve_eps(_dev(q), 0, 64, 8, 0.5, 0.0, 1, 2, want_candidates=True)
+    torch.cuda.synchronize()
+    for x, y in zip(a, b_[:4]):
+        assert np.array_equal(x.cpu().numpy().view(np.uint32), y.cpu().numpy().view(np.uint32))
+    bank.close()
+
+
 @pytest.mark.parametrize("dtype,N,d,nq", [("f32", 5000, 96, 3), ("bf16", 30000, 256, 70), ("f16", 12000, 128, 200), ("bf16", 9000, 64, 1)])
 def test_masked_retrieval_matches_oracle(orc, dtype, N, d, nq):
     rng = np.random.default_rng(N + nq)
