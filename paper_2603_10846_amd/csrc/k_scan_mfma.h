@@ -62,15 +62,38 @@ __device__ __forceinline__ uint32_t pack_bf16x2_hi(float a, float b, float& ra, 
     return h;
 }
 
-// Per-lane choice between two registers by a lane mask (one v_cndmask).  Written as an instruction
-// because the compiler turns the equivalent C++ selects over elements of an accumulator vector into
-// a dynamically indexed vector access, which it expands to a 16-way chain.  The two wait states
-// are the ones gfx950 needs between a vector compare writing the mask and a vector instruction
-// reading it; the compiler does not add them for instructions it cannot see.
-__device__ __forceinline__ float lane_select(float if_clear, float if_set, uint64_t lanes) {
-    float r;
-    asm("s_nop 1\n\tv_cndmask_b32_e64 %0, %1, %2, %3" : "=v"(r) : "v"(if_clear), "v"(if_set), "s"(lanes));
-    return r;
+// Per-lane choice of one of the 16 registers of an accumulator block: register r = 4 * hi + lo of each
+// lane's own (lo, hi), given as lane masks (lo == 1, lo == 3, lo >= 2, hi == 1, hi == 3, hi >= 2).  A
+// two-level tree of 15 v_cndmask (registers cannot be indexed per lane).  Written as instructions because
+// the compiler turns the equivalent C++ selects over elements of an accumulator vector into a
+// dynamically indexed vector access, which it expands to a 16-way chain.  The two wait states at the
+// top are the ones gfx950 needs between a vector compare writing a mask and a vector instruction reading
+// it; the compiler does not add them for instructions it cannot see, and one pair serves all 15.
+__device__ __forceinline__ float lane_select16(const f32x16_t& v, uint64_t lo1, uint64_t lo3, uint64_t lo23,
+                                               uint64_t hi1, uint64_t hi3, uint64_t hi23) {
+    float g0, g1, g2, g3, t;
+    asm("s_nop 1\n\t"
+        "v_cndmask_b32_e64 %[g0], %[a0], %[a1], %[lo1]\n\t"
+        "v_cndmask_b32_e64 %[t], %[a2], %[a3], %[lo3]\n\t"
+        "v_cndmask_b32_e64 %[g0], %[g0], %[t], %[lo23]\n\t"
+        "v_cndmask_b32_e64 %[g1], %[a4], %[a5], %[lo1]\n\t"
+        "v_cndmask_b32_e64 %[t], %[a6], %[a7], %[lo3]\n\t"
+        "v_cndmask_b32_e64 %[g1], %[g1], %[t], %[lo23]\n\t"
+        "v_cndmask_b32_e64 %[g2], %[a8], %[a9], %[lo1]\n\t"
+        "v_cndmask_b32_e64 %[t], %[a10], %[a11], %[lo3]\n\t"
+        "v_cndmask_b32_e64 %[g2], %[g2], %[t], %[lo23]\n\t"
+        "v_cndmask_b32_e64 %[g3], %[a12], %[a13], %[lo1]\n\t"
+        "v_cndmask_b32_e64 %[t], %[a14], %[a15], %[lo3]\n\t"
+        "v_cndmask_b32_e64 %[g3], %[g3], %[t], %[lo23]\n\t"
+        "v_cndmask_b32_e64 %[g0], %[g0], %[g1], %[hi1]\n\t"
+        "v_cndmask_b32_e64 %[g2], %[g2], %[g3], %[hi3]\n\t"
+        "v_cndmask_b32_e64 %[g0], %[g0], %[g2], %[hi23]"
+        : [g0] "=&v"(g0), [g1] "=&v"(g1), [g2] "=&v"(g2), [g3] "=&v"(g3), [t] "=&v"(t)
+        : [a0] "v"(v[0]), [a1] "v"(v[1]), [a2] "v"(v[2]), [a3] "v"(v[3]), [a4] "v"(v[4]), [a5] "v"(v[5]), [a6] "v"(v[6]),
+          [a7] "v"(v[7]), [a8] "v"(v[8]), [a9] "v"(v[9]), [a10] "v"(v[10]), [a11] "v"(v[11]), [a12] "v"(v[12]),
+          [a13] "v"(v[13]), [a14] "v"(v[14]), [a15] "v"(v[15]), [lo1] "s"(lo1), [lo3] "s"(lo3), [lo23] "s"(lo23),
+          [hi1] "s"(hi1), [hi3] "s"(hi3), [hi23] "s"(hi23));
+    return g0;
 }
 
 // Inclusive prefix sum over the 64 lanes of a wavefront (all lanes active): shifts within rows of 16
@@ -549,16 +572,9 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
                 // are served by a loop afterwards.
                 auto pick = [&](int a, int b, int r) __attribute__((always_inline)) {
                     const int lo = r & 3, hi = (r >> 2) & 3;
-                    const uint64_t lo1 = __builtin_amdgcn_ballot_w64(lo == 1), lo3 = __builtin_amdgcn_ballot_w64(lo == 3);
-                    const uint64_t lo23 = __builtin_amdgcn_ballot_w64(lo >= 2);
-                    float g4[4];
-#pragma unroll
-                    for (int k = 0; k < 4; ++k)
-                        g4[k] = lane_select(lane_select(acc[a][b][4 * k], acc[a][b][4 * k + 1], lo1),
-                                            lane_select(acc[a][b][4 * k + 2], acc[a][b][4 * k + 3], lo3), lo23);
-                    return lane_select(lane_select(g4[0], g4[1], __builtin_amdgcn_ballot_w64(hi == 1)),
-                                       lane_select(g4[2], g4[3], __builtin_amdgcn_ballot_w64(hi == 3)),
-                                       __builtin_amdgcn_ballot_w64(hi >= 2));
+                    return lane_select16(acc[a][b], __builtin_amdgcn_ballot_w64(lo == 1), __builtin_amdgcn_ballot_w64(lo == 3),
+                                         __builtin_amdgcn_ballot_w64(lo >= 2), __builtin_amdgcn_ballot_w64(hi == 1),
+                                         __builtin_amdgcn_ballot_w64(hi == 3), __builtin_amdgcn_ballot_w64(hi >= 2));
                 };
                 auto stage_one = [&](int a, int b, int r, float av) __attribute__((always_inline)) {   // lanes with a survivor
                     const int ln = fresh_lane(), half = ln >> 5, l32 = ln & 31;
