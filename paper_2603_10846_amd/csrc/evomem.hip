@@ -87,6 +87,11 @@ struct evomem {
     std::vector<int64_t> prof_rows;
 };
 
+// Clears a few words on the stream (a kernel, not a memset: callers may record their calls into a HIP graph).
+__global__ void k_clear_words(uint32_t* p, int n) {
+    for (int i = threadIdx.x; i < n; i += blockDim.x) p[i] = 0u;
+}
+
 #define HIPCHK(x) do { if ((x) != hipSuccess) return MEM_EHIP; } while (0)
 #define LAUNCHCHK() do { if (hipGetLastError() != hipSuccess) return MEM_EHIP; } while (0)
 
@@ -264,7 +269,9 @@ int mem_reward_stats(evomem_t* h, int stage, double* count, double* mean, double
 
 int mem_reward_stats_reset(evomem_t* h, int stage, void* hip_stream) {
     if (!h || (stage != 0 && stage != 1)) return MEM_EINVAL;
-    HIPCHK(hipMemsetAsync(reward_state(h, stage), 0, 3 * sizeof(double), static_cast<hipStream_t>(hip_stream)));
+    hipLaunchKernelGGL(k_clear_words, dim3(1), dim3(64), 0, static_cast<hipStream_t>(hip_stream),
+                       reinterpret_cast<uint32_t*>(reward_state(h, stage)), (int)(3 * sizeof(double) / sizeof(uint32_t)));
+    LAUNCHCHK();
     return MEM_OK;
 }
 
@@ -574,10 +581,6 @@ extern "C" int mem_retrieve(evomem_t* h, const float* queries_dev, int B, int st
 // device address is looked up once per device and kept.
 static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
 static unsigned char* scratch_ptr[16] = {};
-
-__global__ void k_clear_words(uint32_t* p, int n) {
-    for (int i = threadIdx.x; i < n; i += blockDim.x) p[i] = 0u;
-}
 
 extern "C" int mem_retrieve_static(evomem_t* h, const float* queries_dev, int B, int stage, int k1, int k2, float lambda,
                                    int32_t* out_ids_dev, float* out_scores_dev, int32_t* out_cand_ids_dev,
