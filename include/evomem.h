@@ -110,13 +110,26 @@ int mem_retrieve(evomem_t* h, const float* queries_dev, int B, int stage, int k1
                  int32_t* out_cand_ids_dev, float* out_cand_sims_dev, void* hip_stream);
 
 /*
+ * mem_retrieve by exhaustive selection: the same arguments and the same results, reached without
+ * thresholds or scan passes -- the similarity of EVERY entry to every query is accumulated in fp64
+ * (rounded to fp32 for the selection: entries whose similarities differ by less than 6e-8 rank by id) and
+ * the pool is selected range by range, so no list can overflow whatever the bank holds.  It reads the
+ * bank once per QUERY instead of once per batch (1M x 1024 bf16 entries: about 2 ms per query), so it is
+ * the call for the queries that mem_retrieve_flags reports, and an on-device cross-check of mem_retrieve.
+ * Greedy selection only.  Errors: as mem_retrieve.
+ */
+int mem_retrieve_exact(evomem_t* h, const float* queries_dev, int B, int stage, int k1, int k2,
+                       float lambda, int32_t* out_ids_dev, float* out_scores_dev,
+                       int32_t* out_cand_ids_dev, float* out_cand_sims_dev, void* hip_stream);
+
+/*
  * Per-query status of the latest retrieve call of any kind on this handle (enqueued on the same stream,
  * or ordered after it): copies B words to out_flags_dev (uint32[B]) on the stream, without synchronising.
  * Bit 0 (MEM_FLAG_OVERFLOW): during some scan pass more than 8192 rows of the bank reached the query's
  * running threshold (the k1-th best similarity seen so far, minus a rounding margin) -- a mass of
  * near-duplicates of the pool's last members.  The rows beyond 8192 were not kept, so the pool of such a
  * query may miss members whose similarity ties with its last ones; every other query of the call is
- * exact.  Errors: MEM_EINVAL, MEM_ESTATE (no retrieve yet, or B larger than that call's), MEM_EHIP.
+ * exact, and mem_retrieve_exact answers the flagged ones exactly.  Errors: MEM_EINVAL, MEM_ESTATE (no retrieve yet, or B larger than that call's), MEM_EHIP.
  */
 #define MEM_FLAG_OVERFLOW 1u
 int mem_retrieve_flags(evomem_t* h, uint32_t* out_flags_dev, int B, void* hip_stream);

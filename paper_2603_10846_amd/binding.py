@@ -34,6 +34,8 @@ SYMBOLS = {
                                C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "mem_retrieve_static": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_float,
                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "mem_retrieve_exact": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_float,
+                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "mem_retrieve_flags": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p]),
     "mem_retrieve_eps": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_float, C.c_float,
                                    C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -170,6 +172,18 @@ class MemoryBank:
             ids, scores, cid, csim = out
         _check(self.lib.mem_retrieve(self.h, _ptr(queries), B, stage, k1, k2, lam, _ptr(ids), _ptr(scores),
                                      _ptr(cid), _ptr(csim), _stream()), "mem_retrieve")
+        return ids, scores, cid, csim
+
+    def retrieve_exact(self, queries: torch.Tensor, stage: int, k1: int, k2: int, lam: float, want_candidates: bool = False):
+        """mem_retrieve by exhaustive selection (every entry scored in fp64; no list can overflow)."""
+        assert queries.is_cuda and queries.dtype == torch.float32 and queries.is_contiguous()
+        B = queries.shape[0]
+        ids = torch.empty((B, k2), dtype=torch.int32, device=self.device)
+        scores = torch.empty((B, k2), dtype=torch.float32, device=self.device)
+        cid = torch.empty((B, k1), dtype=torch.int32, device=self.device) if want_candidates else None
+        csim = torch.empty((B, k1), dtype=torch.float32, device=self.device) if want_candidates else None
+        _check(self.lib.mem_retrieve_exact(self.h, _ptr(queries), B, stage, k1, k2, lam, _ptr(ids), _ptr(scores),
+                                           _ptr(cid), _ptr(csim), _stream()), "mem_retrieve_exact")
         return ids, scores, cid, csim
 
     def retrieve_flags(self, B: int) -> torch.Tensor:

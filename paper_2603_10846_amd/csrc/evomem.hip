@@ -426,7 +426,7 @@ extern "C" int mem_plan_levels(int64_t N, int k1, int* stride, int* rho, int* nt
 static int retrieve_impl(evomem_t* h, const float* queries_dev, int B, int stage, int k1, int k2, float lambda,
                          int32_t* out_ids_dev, float* out_scores_dev, int32_t* out_cand_ids_dev,
                          float* out_cand_sims_dev, void* hip_stream, const EpsGreedy& eg, const Mask& mask,
-                         const Scratch& sc, int max_B, int max_k1) {
+                         const Scratch& sc, int max_B, int max_k1, bool exhaustive = false) {
     if (!h || B < 0 || B > max_B || (stage != 0 && stage != 1) || k1 < 1 || k2 < 1 || k2 > k1 || k1 > max_k1)
         return MEM_EINVAL;
     if (!(lambda >= 0.f && lambda <= 1.f)) return MEM_EINVAL;
@@ -455,7 +455,7 @@ static int retrieve_impl(evomem_t* h, const float* queries_dev, int B, int stage
 
     Plan plan{};
     uint32_t cnt0 = 0;      // valid rows of the sparsest pass (a prefix of its last tile may be all that exists)
-    if (h->N > 0) {
+    if (h->N > 0 && !exhaustive) {
         plan = plan_levels(h->N, k1);
         const Level& L0 = plan.lv[0];
         const int64_t last = level_tile(L0, L0.ntiles - 1) * TILE_ROWS;
@@ -479,8 +479,30 @@ static int retrieve_impl(evomem_t* h, const float* queries_dev, int B, int stage
     // Pools of up to 128 with one workgroup per query in the gather (more than 128 queries): the last
     // selection, the re-scoring and the value filter run as one launch (measured on the 1M x 1024 bank at
     // 256 queries: see the kernel).
-    const bool fused_tail = h->N > 0 && k1 <= 128 && B > 128;
-    if (h->N > 0) {
+    const bool fused_tail = h->N > 0 && k1 <= 128 && B > 128 && !exhaustive;
+    if (h->N > 0 && exhaustive) {
+        // every entry's similarity is accumulated in fp64; the bank is walked in ranges that fit a list
+        const int keep = keep_of(k1);
+        const int64_t range_rows = (int64_t)((SURV_CAP - keep) / TILE_ROWS) * TILE_ROWS;
+        int parts = 1;
+        while (parts < 16 && B * parts < 512) parts <<= 1;
+        for (int64_t first = 0; first < h->N; first += range_rows) {
+            const int n_new = (int)(h->N - first < range_rows ? h->N - first : range_rows);
+            hipLaunchKernelGGL(k_exact_fill, dim3(B), dim3(256), 0, st, surv, cnt, (int32_t)first, n_new);
+            LAUNCHCHK();
+            dim3 kgrid((unsigned)B, (unsigned)parts);
+            if (h->dtype == MEM_F32)
+                hipLaunchKernelGGL(k_exact_keys<0>, kgrid, dim3(1024), 0, st, (const void*)h->store, (const float*)qf, (const double*)invq64, surv, (const uint32_t*)cnt, h->nkb, n_new);
+            else if (h->dtype == MEM_BF16)
+                hipLaunchKernelGGL(k_exact_keys<1>, kgrid, dim3(1024), 0, st, (const void*)h->store, (const float*)qf, (const double*)invq64, surv, (const uint32_t*)cnt, h->nkb, n_new);
+            else
+                hipLaunchKernelGGL(k_exact_keys<2>, kgrid, dim3(1024), 0, st, (const void*)h->store, (const float*)qf, (const double*)invq64, surv, (const uint32_t*)cnt, h->nkb, n_new);
+            LAUNCHCHK();
+            hipLaunchKernelGGL(k_exact_select, dim3(B), dim3(1024), 0, st, surv, cnt, thr, (const float*)invq, counters, flags, k1, keep);
+            LAUNCHCHK();
+        }
+    }
+    if (h->N > 0 && !exhaustive) {
         for (int li = 0; li < plan.n; ++li) {
             const Level& L = plan.lv[li];
             const bool prof = h->prof_on && h->prof_n < MAX_PROFILE;
@@ -528,6 +550,8 @@ static int retrieve_impl(evomem_t* h, const float* queries_dev, int B, int stage
             LAUNCHCHK();
             return MEM_OK;
         }
+    }
+    if (h->N > 0) {
         // a query's candidates are split over several workgroups when there are few queries, so that the
         // gather occupies the whole device
         // (measured: 151 -> 102 us at B = 128, d = 4096; no gain at B = 256)
@@ -604,6 +628,15 @@ extern "C" int mem_retrieve_static(evomem_t* h, const float* queries_dev, int B,
     return retrieve_impl(h, queries_dev, B, stage, k1, k2, lambda, out_ids_dev, out_scores_dev, out_cand_ids_dev,
                          out_cand_sims_dev, hip_stream, greedy, Mask{nullptr, nullptr, nullptr},
                          Scratch{scratch_ptr[cur], STATIC_W, keep_of(STATIC_MAX_K1)}, STATIC_MAX_B, STATIC_MAX_K1);
+}
+
+extern "C" int mem_retrieve_exact(evomem_t* h, const float* queries_dev, int B, int stage, int k1, int k2, float lambda,
+                                  int32_t* out_ids_dev, float* out_scores_dev, int32_t* out_cand_ids_dev,
+                                  float* out_cand_sims_dev, void* hip_stream) {
+    if (!h) return MEM_EINVAL;
+    const EpsGreedy greedy{0, 0, 0, nullptr};
+    return retrieve_impl(h, queries_dev, B, stage, k1, k2, lambda, out_ids_dev, out_scores_dev, out_cand_ids_dev,
+                         out_cand_sims_dev, hip_stream, greedy, Mask{nullptr, nullptr, nullptr}, own_scratch(h), h->max_B, h->max_k1, true);
 }
 
 extern "C" int mem_retrieve_flags(evomem_t* h, uint32_t* out_flags_dev, int B, void* hip_stream) {

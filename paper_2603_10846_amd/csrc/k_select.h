@@ -201,7 +201,7 @@ __device__ __forceinline__ void rescore_one_query(const int b, const int part, c
                                                   const void* store_, const float* qf,
                                                   const double* invq64, std::conditional_t<REQUANT, uint64_t, const uint64_t>* surv,
                                                   const uint32_t* cnt, double* exact,
-                                                  int nkb, int exact_stride) {
+                                                  int nkb, int exact_stride, int begin = 0) {
     // One workgroup per query; 16 lanes per candidate row, so a wavefront works on four rows at a
     // time and every lane has up to eight 16-byte loads in flight.
     const int sub = threadIdx.x & 15, grp = threadIdx.x >> 4;   // grp 0..63
@@ -210,7 +210,7 @@ __device__ __forceinline__ void rescore_one_query(const int b, const int part, c
     constexpr int EPC = DT == 0 ? 4 : 8;                 // elements per 16-byte chunk
     const int nch = nkb * KB / EPC;                      // chunks per row
     // (`parts` workgroups share a query: workgroup `part` takes the candidate groups part, part + parts, ...)
-    for (int j0 = 64 * part; j0 < n; j0 += 64 * parts) {   // uniform trip count: the shuffles below need all lanes
+    for (int j0 = begin + 64 * part; j0 < n; j0 += 64 * parts) {   // uniform trip count: the shuffles below need all lanes
         const int j = j0 + grp;
         const bool live = j < n;
         const int32_t id = live ? key_id(surv[(int64_t)b * SURV_CAP + j]) : 0;
@@ -293,6 +293,35 @@ __global__ __launch_bounds__(1024) void k_rescore(const void* __restrict__ store
                                                   const uint32_t* __restrict__ cnt, double* __restrict__ exact,
                                                   int nkb, int exact_stride) {
     rescore_one_query<DT>((int)blockIdx.x, (int)blockIdx.y, (int)gridDim.y, store_, qf, invq64, surv, cnt, exact, nkb, exact_stride);
+}
+
+// ---- exhaustive selection (mem_retrieve_exact): no threshold, no scan, no list that can overflow ----
+// The bank is walked in ranges small enough that the carried candidates plus every row of the range fit
+// a survivor list.  Per range: (1) the range's ids are appended to every query's list, (2) each appended
+// entry gets its key from the similarity accumulated in fp64 (rounded to fp32), (3) the list is cut back to
+// the k1 best keys plus those within two fp32 roundings of the k1-th (or, if that band is crowded, to
+// exactly the k1 best: lower ids first among equal similarities).  The top-k1 of a union is the top-k1 of
+// the parts' top-k1, so after the last range the list holds the pool.
+__global__ __launch_bounds__(256) void k_exact_fill(uint64_t* __restrict__ surv, uint32_t* __restrict__ cnt, int32_t first_id, int n_new) {
+    const int b = (int)blockIdx.x;
+    const uint32_t have = cnt[b];
+    __syncthreads();                                    // every lane has read the old count
+    for (int i = threadIdx.x; i < n_new; i += 256) surv[(int64_t)b * SURV_CAP + have + i] = pack_key(0.f, first_id + i);
+    if (threadIdx.x == 0) cnt[b] = have + (uint32_t)n_new;
+}
+
+template <int DT>
+__global__ __launch_bounds__(1024) void k_exact_keys(const void* __restrict__ store_, const float* __restrict__ qf,
+                                                     const double* __restrict__ invq64, uint64_t* __restrict__ surv,
+                                                     const uint32_t* __restrict__ cnt, int nkb, int n_new) {
+    const int b = (int)blockIdx.x;
+    rescore_one_query<DT, true>(b, (int)blockIdx.y, (int)gridDim.y, store_, qf, invq64, surv, cnt, nullptr, nkb, 0, (int)cnt[b] - n_new);
+}
+
+__global__ __launch_bounds__(1024) void k_exact_select(uint64_t* __restrict__ surv, uint32_t* __restrict__ cnt, float* __restrict__ thr,
+                                                       const float* __restrict__ invq, uint32_t* __restrict__ counters,
+                                                       uint32_t* __restrict__ flags, int k1, int keep_max) {
+    select_one_query((int)blockIdx.x, surv, cnt, thr, invq, counters, flags, k1, EXACT_KEY_MARGIN, 0, keep_max, SEL_EXACT);
 }
 
 constexpr int RERANK_T = 256;

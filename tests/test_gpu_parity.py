@@ -364,6 +364,40 @@ def test_survivor_list_overflow_is_counted(orc):
     out2 = parity.gpu_retrieve(bank, torch, q[safe], 0, 64, 8, 0.0)
     parity.check_retrieve(orc, st, qr[safe], np.zeros(len(rows), np.float32), 64, 8, 0.0, out2)
     assert bank.counters()[1] == before and not bank.retrieve_flags(len(safe)).cpu().numpy().any()
+    # the exhaustive call answers the flagged query exactly: the copies tie exactly, so the pool is their 64 lowest ids
+    ids, sc, cid, csim = bank.retrieve_exact(_dev(q), 0, 64, 8, 0.0, want_candidates=True)
+    torch.cuda.synchronize()
+    ex = {"ids": ids.cpu().numpy(), "scores": sc.cpu().numpy(), "cand_ids": cid.cpu().numpy(), "cand_sims": csim.cpu().numpy()}
+    assert ex["cand_ids"][0].tolist() == sorted(copies)[:64]
+    stats = parity.check_retrieve(orc, st, qr, np.zeros(len(rows), np.float32), 64, 8, 0.0, ex)
+    assert stats["boundary_swaps"] == 0 and stats["order_swaps"] == 0 and stats["final_swaps"] == 0
+    assert not bank.retrieve_flags(len(q)).cpu().numpy().any() and bank.counters()[1] == before
+    bank.close()
+
+
+@pytest.mark.parametrize("dtype,N,d,nq,k1,k2", [("bf16", 30000, 128, 7, 64, 8), ("f32", 9000, 72, 2, 256, 32), ("f16", 20000, 64, 70, 300, 16),
+                                                ("bf16", 100, 64, 3, 128, 16), ("f16", 9000, 64, 5, 2048, 64)])
+def test_exhaustive_retrieve_matches_oracle_and_the_scan(orc, dtype, N, d, nq, k1, k2):
+    rng = np.random.default_rng([17, N, nq, k1])
+    rows = _unit(rng, N, d) * rng.uniform(0.5, 2.0, (N, 1)).astype(np.float32)
+    rows[N // 2] = rows[7]
+    q = _unit(rng, nq, d)
+    q[0] = rows[7]
+    qtab = rng.uniform(-1, 1, (2, N)).astype(np.float32)
+    print(f"exhaustive {dtype} N={N} B={nq} k1={k1}", flush=True)
+    bank = _make_bank(dtype, rows, qtab, max_B=max(nq, 8), max_k1=max(k1, 256))
+    ids, sc, cid, csim = bank.retrieve_exact(_dev(q), 1, k1, k2, 0.5, want_candidates=True)
+    torch.cuda.synchronize()
+    ex = {"ids": ids.cpu().numpy(), "scores": sc.cpu().numpy(), "cand_ids": cid.cpu().numpy(), "cand_sims": csim.cpu().numpy()}
+    st, qr = orc.round_to_store(rows, DT[dtype]), orc.round_to_store(q, DT[dtype])
+    stats = parity.check_retrieve(orc, st, qr, qtab[1], k1, k2, 0.5, ex)
+    assert stats["boundary_swaps"] == 0 and stats["final_swaps"] == 0
+    assert ex["cand_ids"][0, 0] == 7 and (N <= 7 or ex["cand_ids"][0, 1] == N // 2)
+    # the ordinary call agrees bit for bit on such data (no ties within fp32 resolution at a pool's edge)
+    ref = parity.gpu_retrieve(bank, torch, q, 1, k1, k2, 0.5)
+    for k in ex:
+        assert np.array_equal(ex[k].view(np.uint32), ref[k].view(np.uint32)), k
+    assert bank.counters() == (0, 0)
     bank.close()
 
 
@@ -549,6 +583,21 @@ def test_clustered_workload_full_size(orc):
         assert np.all(np.abs(gpu["cand_sims"][b][:8] - true) <= 2e-2 * np.abs(true))
     g0 = parity.gpu_retrieve(bank, torch, q, 0, w.k1, w.k2, 0.0)
     assert np.array_equal(g0["ids"], g0["cand_ids"][:, :w.k2])          # lambda = 0: similarity ranking
+    # the exhaustive call (every entry scored in fp64, no thresholds) on four of the queries: judged by the oracle
+    # like the scan's result, and here equal to it
+    import time
+    qd = _dev(q[:4])
+    bank.retrieve_exact(qd, 0, w.k1, w.k2, w.lam)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ids, sc, cid, csim = bank.retrieve_exact(qd, 0, w.k1, w.k2, w.lam, want_candidates=True)
+    torch.cuda.synchronize()
+    print(f"exhaustive retrieve, 4 queries over {w.N} entries: {(time.perf_counter() - t0) * 1e3:.1f} ms", flush=True)
+    ex = {"ids": ids.cpu().numpy(), "scores": sc.cpu().numpy(), "cand_ids": cid.cpu().numpy(), "cand_sims": csim.cpu().numpy()}
+    qr4 = orc.round_to_store(q[:4], DT[w.dtype])
+    parity.check_retrieve(orc, rounded, qr4, qtab[0], w.k1, w.k2, w.lam, ex, threads=4)
+    for k in ex:
+        assert np.array_equal(ex[k].view(np.uint32), gpu[k][:4].view(np.uint32)), k
     assert bank.counters() == (0, 0)
     bank.close()
 
