@@ -103,6 +103,14 @@ def other_configs(torch, binding, synth, clustered_bank, clustered_w):
         w = synth.scaled(clustered_w, B=B)
         r = retrieve_figures(torch, clustered_bank, todev(synth.queries(w)), synth.DRAFT, w, 2)
         res.append({"workload": f"clustered bank, B={B}", **r})
+    # the exhaustive retrieve (every entry scored in fp64; the always-exact path for flagged queries): four queries
+    w4 = synth.scaled(clustered_w, B=4)
+    q4 = todev(synth.queries(w4))
+    ex_ms = time_calls(torch, lambda: clustered_bank.retrieve_exact(q4, synth.DRAFT, w4.k1, w4.k2, w4.lam), 5, warm=2)
+    res.append({"workload": "clustered bank, mem_retrieve_exact, B=4", "B": 4, "retrieve_ms": round(ex_ms, 3),
+                "queries_per_s": round(4 / (ex_ms * 1e-3), 1),
+                "store_GBps": round(4 * clustered_bank.size() * w4.d * 2 / (ex_ms * 1e-3) / 1e9, 1),
+                "note": "reads the bank once per query"})
     # mid: fp32 rows
     w = synth.MID
     bank = binding.MemoryBank(w.d, w.dtype, w.N, max_B=w.B, max_k1=w.k1)
