@@ -20,19 +20,19 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 COUNTER_SUMMARY = os.path.join(ROOT, "profiles", "k_scan_mfma_clustered_hbm_counters.txt")
+KERNEL_SOURCES = ("k_scan_mfma.h", "k_scan_gemv.h", "layout.h")      # what the scan kernel is compiled from
 
 
 def measured_traffic(workload):
     """HBM bytes per launch of the densest scan pass from the committed counter summary, or None when
-    it is for another workload or the kernel sources have changed since the counters were taken."""
-    import glob
+    it is for another workload or the kernel's sources have changed since the counters were taken."""
     import hashlib
     if workload != "clustered" or not os.path.exists(COUNTER_SUMMARY):
         return None
     h = hashlib.sha256()
-    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2603_10846_amd", "csrc", "*"))):
-        h.update(os.path.basename(f).encode())
-        h.update(open(f, "rb").read())
+    for name in KERNEL_SOURCES:
+        h.update(name.encode())
+        h.update(open(os.path.join(ROOT, "paper_2603_10846_amd", "csrc", name), "rb").read())
     fields = dict(l.split(": ", 1) for l in open(COUNTER_SUMMARY).read().splitlines() if ": " in l and " " not in l.split(": ")[0])
     if fields.get("kernel_source_sha256") != h.hexdigest():
         return None

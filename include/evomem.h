@@ -114,7 +114,7 @@ int mem_retrieve(evomem_t* h, const float* queries_dev, int B, int stage, int k1
  * thresholds or scan passes -- the similarity of EVERY entry to every query is accumulated in fp64
  * (rounded to fp32 for the selection: entries whose similarities differ by less than 6e-8 rank by id) and
  * the pool is selected range by range, so no list can overflow whatever the bank holds.  It reads the
- * bank once per QUERY instead of once per batch (1M x 1024 bf16 entries: about 2 ms per query), so it is
+ * bank once per QUERY instead of once per batch (1M x 1024 bf16 entries: about 1 ms per query), so it is
  * the call for the queries that mem_retrieve_flags reports, and an on-device cross-check of mem_retrieve.
  * Greedy selection only.  Errors: as mem_retrieve.
  */

@@ -485,7 +485,7 @@ static int retrieve_impl(evomem_t* h, const float* queries_dev, int B, int stage
         const int keep = keep_of(k1);
         const int64_t range_rows = (int64_t)((SURV_CAP - keep) / TILE_ROWS) * TILE_ROWS;
         int parts = 1;
-        while (parts < 16 && B * parts < 512) parts <<= 1;
+        while (parts < 64 && B * parts < 512) parts <<= 1;       // few queries: each query's range is shared by many workgroups
         for (int64_t first = 0; first < h->N; first += range_rows) {
             const int n_new = (int)(h->N - first < range_rows ? h->N - first : range_rows);
             hipLaunchKernelGGL(k_exact_fill, dim3(B), dim3(256), 0, st, surv, cnt, (int32_t)first, n_new);
