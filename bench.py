@@ -379,10 +379,14 @@ def main():
                "nproc": os.cpu_count(), "openmp_max_threads": orc.max_threads()}
         del rounded
 
-    ceiling = read_ceiling(torch, bank)
-    configs = None
-    if args.workload == "clustered" and not args.batch and not args.no_other_configs:
-        configs = other_configs(torch, binding, synth, bank, w)
+    # the extras below are not part of `value`: a failure in them must not cost the line
+    ceiling, configs, extras_error = None, None, None
+    try:
+        ceiling = read_ceiling(torch, bank)
+        if args.workload == "clustered" and not args.batch and not args.no_other_configs:
+            configs = other_configs(torch, binding, synth, bank, w)
+    except Exception as e:                                      # noqa: BLE001 (reported in the line)
+        extras_error = f"{type(e).__name__}: {e}"
 
     print(json.dumps({
         "metric": "retrieval queries/sec at N=1M,d=1024 + achieved HBM GB/s (% of peak)"
@@ -395,7 +399,7 @@ def main():
                                f"(the bank holds N entries before the first step and grows by B per step)",
                    "N": w.N, "N_after_last_step": w.N + (steps + warm) * w.B, "d": w.d, "B": w.B, "k1": w.k1, "k2": w.k2},
         "roofline": roofline, "cpu_baseline": cpu, "breakdown": breakdown, "read_ceiling": ceiling, "configs": configs,
-        "untimed_calls_before_timing": {"steps": warm, "read_only_retrieves": settle},
+        "untimed_calls_before_timing": {"steps": warm, "read_only_retrieves": settle}, "extras_error": extras_error,
     }))
     bank.close()
 
