@@ -76,7 +76,7 @@ size_t mem_workspace_bytes(int d, int dtype, int64_t capacity, int max_B, int ma
  *   invnorm_dev    float[capacity rounded up to a multiple of 256]
  *   q_dev          float[2][capacity]: row 0 = drafting values Q_1, row 1 = refining values Q_2
  *   workspace_dev  mem_workspace_bytes() bytes, 256-byte aligned
- *   device         HIP device ordinal the buffers live on
+ *   device         HIP device ordinal the buffers live on, 0..15; it becomes the calling thread's current device
  * Errors: MEM_EINVAL, MEM_EWORKSPACE, MEM_EHIP.
  */
 int mem_create(evomem_t** out, int d, int dtype, int64_t capacity,

@@ -6,6 +6,7 @@
 #include <cstdio>
 #include <cstring>
 #include <new>
+#include <type_traits>
 #include <vector>
 
 #include "../../include/evomem.h"
@@ -28,7 +29,17 @@ namespace {
 constexpr int MAX_PROFILE = 4096;
 constexpr int GEMV_MAX_B = 4;       // fp32 stores: at most this many queries use the VALU scan
 
+constexpr int MAX_DEVICES = 16;     // per-device set-up flags and scratch addresses are kept in arrays of this size
+
 constexpr int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+// Calls f with the store type as a compile-time constant (0 fp32, 1 bf16, 2 fp16: the kernels' DT).
+template <class F>
+void with_store_type(int dtype, F&& f) {
+    if (dtype == MEM_F32) f(std::integral_constant<int, 0>{});
+    else if (dtype == MEM_BF16) f(std::integral_constant<int, 1>{});
+    else f(std::integral_constant<int, 2>{});
+}
 
 struct Workspace {   // byte offsets into a scratch area (the caller's workspace, or the library's own array)
     size_t counters, qf, qop, invq, invq64, thr, cnt, flags, surv, exact, total;
@@ -112,7 +123,7 @@ int mem_create(evomem_t** out, int d, int dtype, int64_t capacity, void* store_d
     if (!out) return MEM_EINVAL;
     *out = nullptr;
     if (!shape_ok(d, dtype, capacity) || !store_dev || !invnorm_dev || !q_dev || !workspace_dev) return MEM_EINVAL;
-    if (max_B < 1 || max_B > MEM_MAX_B || max_k1 < 1 || max_k1 > MEM_MAX_K1 || device < 0) return MEM_EINVAL;
+    if (max_B < 1 || max_B > MEM_MAX_B || max_k1 < 1 || max_k1 > MEM_MAX_K1 || device < 0 || device >= MAX_DEVICES) return MEM_EINVAL;
     if (((uintptr_t)store_dev | (uintptr_t)workspace_dev) & 255) return MEM_EINVAL;
     Workspace w = carve(d, dtype, max_B, max_k1);
     if (workspace_bytes < w.total) return MEM_EWORKSPACE;
@@ -219,8 +230,13 @@ int mem_profile_enable(evomem_t* h, int on) {
     if (on && h->ev.empty()) {
         h->ev.resize(2 * MAX_PROFILE);
         h->prof_rows.resize(MAX_PROFILE);
-        for (auto& e : h->ev)
-            if (hipEventCreate(&e) != hipSuccess) return MEM_EHIP;
+        for (size_t i = 0; i < h->ev.size(); ++i)
+            if (hipEventCreate(&h->ev[i]) != hipSuccess) {       // leave no half-built set behind
+                for (size_t j = 0; j < i; ++j) (void)hipEventDestroy(h->ev[j]);
+                h->ev.clear();
+                h->prof_rows.clear();
+                return MEM_EHIP;
+            }
     }
     h->prof_on = on != 0;      // the records kept so far stay until they are read
     return MEM_OK;
@@ -338,18 +354,18 @@ int launch_mfma(evomem* h, const Scratch& sc, hipStream_t st, int Bp, const Leve
     constexpr int QT = 32 * MQ * WQ;
     constexpr int lds = scan_mfma_lds_bytes<QT, MASKED>();
     auto kern = k_scan_mfma<DT, MQ, WQ, MR, WR, MASKED, STREAM>;
-    static int resident[16] = {};          // workgroups of this kernel the whole device holds at once
-    if (!resident[h->device & 15]) {
+    static int resident[MAX_DEVICES] = {};          // workgroups of this kernel the whole device holds at once
+    if (!resident[h->device]) {
         HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds));
         int per_cu = 0, cus = 0;
         HIPCHK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(kern), 64 * WQ * WR, lds));
         HIPCHK(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, h->device));
         if (per_cu < 1 || cus < 8) return MEM_EHIP;
-        resident[h->device & 15] = per_cu * cus;
+        resident[h->device] = per_cu * cus;
     }
     // persistent launch: per XCD, `groups` tile walkers for each of the nqt query tiles
     const int nqt = Bp / QT;
-    int groups = resident[h->device & 15] / 8 / nqt;
+    int groups = resident[h->device] / 8 / nqt;
     if (groups < 1) groups = 1;
     if (groups > (L.ntiles + 7) / 8) groups = (L.ntiles + 7) / 8;
     dim3 grid((unsigned)(8 * nqt * groups)), block(64 * WQ * WR);
@@ -462,12 +478,10 @@ static int retrieve_impl(evomem_t* h, const float* queries_dev, int B, int stage
         const int64_t in_last = h->N - last < TILE_ROWS ? h->N - last : TILE_ROWS;
         cnt0 = (uint32_t)((int64_t)(L0.ntiles - 1) * TILE_ROWS + in_last);
     }
-    if (h->dtype == MEM_F32)
-        hipLaunchKernelGGL(k_prep_queries<0>, dim3(Bp), dim3(256), 0, st, queries_dev, B, Bp, h->d, h->nkb, qf, qop, invq, invq64, thr, cnt, flags, cnt0);
-    else if (h->dtype == MEM_BF16)
-        hipLaunchKernelGGL(k_prep_queries<1>, dim3(Bp), dim3(256), 0, st, queries_dev, B, Bp, h->d, h->nkb, qf, qop, invq, invq64, thr, cnt, flags, cnt0);
-    else
-        hipLaunchKernelGGL(k_prep_queries<2>, dim3(Bp), dim3(256), 0, st, queries_dev, B, Bp, h->d, h->nkb, qf, qop, invq, invq64, thr, cnt, flags, cnt0);
+    with_store_type(h->dtype, [&](auto dt) {
+        hipLaunchKernelGGL(k_prep_queries<decltype(dt)::value>, dim3(Bp), dim3(256), 0, st, queries_dev, B, Bp, h->d, h->nkb, qf, qop,
+                           invq, invq64, thr, cnt, flags, cnt0);
+    });
     LAUNCHCHK();
 
     // rounding margin of the scan's fp32 similarities
@@ -491,12 +505,10 @@ static int retrieve_impl(evomem_t* h, const float* queries_dev, int B, int stage
             hipLaunchKernelGGL(k_exact_fill, dim3(B), dim3(256), 0, st, surv, cnt, (int32_t)first, n_new);
             LAUNCHCHK();
             dim3 kgrid((unsigned)B, (unsigned)parts);
-            if (h->dtype == MEM_F32)
-                hipLaunchKernelGGL(k_exact_keys<0>, kgrid, dim3(1024), 0, st, (const void*)h->store, (const float*)qf, (const double*)invq64, surv, (const uint32_t*)cnt, h->nkb, n_new);
-            else if (h->dtype == MEM_BF16)
-                hipLaunchKernelGGL(k_exact_keys<1>, kgrid, dim3(1024), 0, st, (const void*)h->store, (const float*)qf, (const double*)invq64, surv, (const uint32_t*)cnt, h->nkb, n_new);
-            else
-                hipLaunchKernelGGL(k_exact_keys<2>, kgrid, dim3(1024), 0, st, (const void*)h->store, (const float*)qf, (const double*)invq64, surv, (const uint32_t*)cnt, h->nkb, n_new);
+            with_store_type(h->dtype, [&](auto dt) {
+                hipLaunchKernelGGL(k_exact_keys<decltype(dt)::value>, kgrid, dim3(1024), 0, st, (const void*)h->store, (const float*)qf,
+                                   (const double*)invq64, surv, (const uint32_t*)cnt, h->nkb, n_new);
+            });
             LAUNCHCHK();
             hipLaunchKernelGGL(k_exact_select, dim3(B), dim3(1024), 0, st, surv, cnt, thr, (const float*)invq, counters, flags, k1, keep);
             LAUNCHCHK();
@@ -526,12 +538,11 @@ static int retrieve_impl(evomem_t* h, const float* queries_dev, int B, int stage
             if (li == plan.n - 1) {
                 if (fused_tail) break;                              // the last selection runs inside the fused kernel below
                 // the last selection refines a crowded band with exactly accumulated similarities
-#define EVK_SELF(DT) hipLaunchKernelGGL(k_select_final<DT>, dim3(B), dim3(1024), 0, st, surv, cnt, thr, (const float*)invq, counters, flags, k1, \
-                margin, mask.tags != nullptr, keep_of(k1), (const void*)h->store, (const float*)qf, (const double*)invq64, h->nkb)
-                if (h->dtype == MEM_F32) EVK_SELF(0);
-                else if (h->dtype == MEM_BF16) EVK_SELF(1);
-                else EVK_SELF(2);
-#undef EVK_SELF
+                with_store_type(h->dtype, [&](auto dt) {
+                    hipLaunchKernelGGL(k_select_final<decltype(dt)::value>, dim3(B), dim3(1024), 0, st, surv, cnt, thr, (const float*)invq,
+                                       counters, flags, k1, margin, mask.tags != nullptr, keep_of(k1), (const void*)h->store,
+                                       (const float*)qf, (const double*)invq64, h->nkb);
+                });
             } else {
                 hipLaunchKernelGGL(k_select, dim3(B), dim3(1024), 0, st, surv, cnt, thr, (const float*)invq, counters, flags, k1, margin,
                                    mask.tags != nullptr, keep_of(k1));
@@ -540,13 +551,12 @@ static int retrieve_impl(evomem_t* h, const float* queries_dev, int B, int stage
         }
         if (fused_tail) {
             const float* qs = (const float*)(h->q + (int64_t)stage * h->capacity);
-#define EVK_TAIL(DT) hipLaunchKernelGGL(k_select_rescore_rerank<DT>, dim3(B), dim3(1024), 0, st, surv, cnt, thr, (const float*)invq, counters, \
-                flags, k1, margin, mask.tags != nullptr, keep_of(k1), (const void*)h->store, (const float*)qf, (const double*)invq64, exact, h->nkb,      \
-                exact_stride, qs, k2, (double)lambda, out_ids_dev, out_scores_dev, out_cand_ids_dev, out_cand_sims_dev, eg)
-            if (h->dtype == MEM_F32) EVK_TAIL(0);
-            else if (h->dtype == MEM_BF16) EVK_TAIL(1);
-            else EVK_TAIL(2);
-#undef EVK_TAIL
+            with_store_type(h->dtype, [&](auto dt) {
+                hipLaunchKernelGGL(k_select_rescore_rerank<decltype(dt)::value>, dim3(B), dim3(1024), 0, st, surv, cnt, thr,
+                                   (const float*)invq, counters, flags, k1, margin, mask.tags != nullptr, keep_of(k1),
+                                   (const void*)h->store, (const float*)qf, (const double*)invq64, exact, h->nkb, exact_stride, qs, k2,
+                                   (double)lambda, out_ids_dev, out_scores_dev, out_cand_ids_dev, out_cand_sims_dev, eg);
+            });
             LAUNCHCHK();
             return MEM_OK;
         }
@@ -558,12 +568,10 @@ static int retrieve_impl(evomem_t* h, const float* queries_dev, int B, int stage
         int rsplit = 1;
         while (B <= 128 && rsplit < 8 && B * rsplit < 512) rsplit <<= 1;
         dim3 rgrid((unsigned)B, (unsigned)rsplit);
-        if (h->dtype == MEM_F32)
-            hipLaunchKernelGGL(k_rescore<0>, rgrid, dim3(1024), 0, st, (const void*)h->store, (const float*)qf, (const double*)invq64, (const uint64_t*)surv, (const uint32_t*)cnt, exact, h->nkb, exact_stride);
-        else if (h->dtype == MEM_BF16)
-            hipLaunchKernelGGL(k_rescore<1>, rgrid, dim3(1024), 0, st, (const void*)h->store, (const float*)qf, (const double*)invq64, (const uint64_t*)surv, (const uint32_t*)cnt, exact, h->nkb, exact_stride);
-        else
-            hipLaunchKernelGGL(k_rescore<2>, rgrid, dim3(1024), 0, st, (const void*)h->store, (const float*)qf, (const double*)invq64, (const uint64_t*)surv, (const uint32_t*)cnt, exact, h->nkb, exact_stride);
+        with_store_type(h->dtype, [&](auto dt) {
+            hipLaunchKernelGGL(k_rescore<decltype(dt)::value>, rgrid, dim3(1024), 0, st, (const void*)h->store, (const float*)qf,
+                               (const double*)invq64, (const uint64_t*)surv, (const uint32_t*)cnt, exact, h->nkb, exact_stride);
+        });
         LAUNCHCHK();
     }
     if (k1 <= 128) {                       // counting ranks is quadratic: measured faster than sorting up to here
@@ -574,11 +582,11 @@ static int retrieve_impl(evomem_t* h, const float* queries_dev, int B, int stage
         int cap = 2;
         while (cap < keep_of(k1)) cap <<= 1;
         const size_t lds = rerank_big_lds(cap, k1, k2);
-        static bool lds_set[16] = {};
-        if (!lds_set[h->device & 15]) {
+        static bool lds_set[MAX_DEVICES] = {};
+        if (!lds_set[h->device]) {
             HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void*>(k_rerank_big), hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)rerank_big_lds(4096, BIG_K1_MAX, BIG_K1_MAX)));
-            lds_set[h->device & 15] = true;
+            lds_set[h->device] = true;
         }
         hipLaunchKernelGGL(k_rerank_big, dim3(B), dim3(BIG_T), lds, st, (const uint64_t*)surv, (const uint32_t*)cnt,
                            (const double*)exact, exact_stride, (const float*)(h->q + (int64_t)stage * h->capacity), k1, k2,
@@ -604,7 +612,7 @@ extern "C" int mem_retrieve(evomem_t* h, const float* queries_dev, int B, int st
 // as long as the library is loaded.  In host code the array's name only stands for the symbol; its
 // device address is looked up once per device and kept.
 static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
-static unsigned char* scratch_ptr[16] = {};
+static unsigned char* scratch_ptr[MAX_DEVICES] = {};
 
 extern "C" int mem_retrieve_static(evomem_t* h, const float* queries_dev, int B, int stage, int k1, int k2, float lambda,
                                    int32_t* out_ids_dev, float* out_scores_dev, int32_t* out_cand_ids_dev,
@@ -613,7 +621,7 @@ extern "C" int mem_retrieve_static(evomem_t* h, const float* queries_dev, int B,
     if (h->nkb * KB > STATIC_MAX_D) return MEM_EINVAL;            // B and k1 are checked against their limits below
     int cur = -1;
     HIPCHK(hipGetDevice(&cur));
-    if (cur != h->device || cur < 0 || cur >= 16) return MEM_ESTATE;
+    if (cur != h->device) return MEM_ESTATE;
     if (!scratch_ptr[cur]) {                                      // first call on this device
         unsigned char* p = nullptr;
         HIPCHK(hipGetSymbolAddress(reinterpret_cast<void**>(&p), HIP_SYMBOL(scratch)));
@@ -710,11 +718,11 @@ extern "C" int mem_update_q(evomem_t* h, const int32_t* ids_dev, int64_t M, int 
     if (!ids_dev || !rewards_dev) return MEM_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     uint32_t* counters = (uint32_t*)(h->ws + h->w.counters);
-    static bool lds_set[16] = {};          // the kernel's LDS list can exceed the default 64 KB limit
-    if (!lds_set[h->device & 15]) {
+    static bool lds_set[MAX_DEVICES] = {};          // the kernel's LDS list can exceed the default 64 KB limit
+    if (!lds_set[h->device]) {
         HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void*>(k_update_q), hipFuncAttributeMaxDynamicSharedMemorySize,
                                    (UPD_CHUNK + UPD_PAD) * 8));
-        lds_set[h->device & 15] = true;
+        lds_set[h->device] = true;
     }
     for (int64_t off = 0; off < M; off += UPD_CHUNK) {
         int m = (int)(M - off < UPD_CHUNK ? M - off : UPD_CHUNK);

@@ -58,6 +58,7 @@ def test_argument_errors_without_gpu(lib):
     assert create(store=None) == B.MEM_EINVAL and create(q=None) == B.MEM_EINVAL
     assert create(store=C.c_void_p(1000)) == B.MEM_EINVAL                      # misaligned
     assert create(mb=0) == B.MEM_EINVAL and create(mk=3000) == B.MEM_EINVAL and create(dev=-1) == B.MEM_EINVAL
+    assert create(dev=16) == B.MEM_EINVAL                                      # device ordinals 0..15
     assert create(wbytes=wb - 1) == B.MEM_EWORKSPACE
     assert h.value is None
     # null handle everywhere
