@@ -21,6 +21,10 @@
  *     library's calls must come from one host thread at a time (it keeps small per-device caches,
  *     such as how many workgroups of a kernel the device holds, without locks).
  *   - No call synchronises with the host except those documented to do so.
+ *   - mem_retrieve (and its variants), mem_update_q, mem_retrieve_flags, mem_shape_rewards and
+ *     mem_select_by_q only launch kernels and device-to-device copies on the given stream: once a first
+ *     call of each has run on the device (it does per-device set-up), they can be recorded into a HIP
+ *     graph and replayed.  mem_append cannot: it counts the bank's entries on the host.
  *   - Entry ids are dense int32: 0,1,2,... in append order, never reused (the bank only grows).
  *   - Similarity is the cosine between the STORED vectors: rows and queries are rounded to the
  *     bank's element type (round-to-nearest-even) first; accumulation is fp32 or wider and the

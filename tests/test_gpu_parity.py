@@ -332,6 +332,61 @@ def test_calls_on_a_side_stream_and_two_banks_at_once(orc):
     bank_b.close()
 
 
+@pytest.mark.parametrize("dtype,N,d,nq,k1,k2", [("f32", 4096, 768, 1, 32, 4), ("bf16", 20000, 256, 40, 64, 8), ("f16", 30000, 128, 200, 128, 16)])
+def test_retrieve_and_update_replayed_from_a_hip_graph(orc, dtype, N, d, nq, k1, k2):
+    """The hot calls launch kernels and nothing else (no allocation, no wait, no memset), so a caller can
+    record them into a HIP graph once the first calls have done their per-device set-up.  Four replays
+    with new queries each, eager work and waits in between: every replay must equal the same calls
+    issued eagerly on a twin bank, bit for bit (outputs and the value table), and the oracle."""
+    rng = np.random.default_rng([DT[dtype], N, d, nq, 5])
+    rows = _unit(rng, N, d)
+    qtab = rng.uniform(-1, 1, (2, N)).astype(np.float32)
+    rewards = _dev(rng.uniform(0, 1, nq * k2).astype(np.float32))
+    eager = _make_bank(dtype, rows, qtab, max_B=max(nq, 8), max_k1=128)
+    graphed = _make_bank(dtype, rows, qtab, max_B=max(nq, 8), max_k1=128)
+    q_in = _dev(_unit(rng, nq, d))
+    out = (torch.empty((nq, k2), dtype=torch.int32, device="cuda:0"), torch.empty((nq, k2), dtype=torch.float32, device="cuda:0"),
+           torch.empty((nq, k1), dtype=torch.int32, device="cuda:0"), torch.empty((nq, k1), dtype=torch.float32, device="cuda:0"))
+    flags = torch.empty(nq, dtype=torch.int32, device="cuda:0")
+
+    def step(bank, q, o):
+        bank.retrieve(q, 1, k1, k2, 0.5, out=o)
+        bank.update_q(o[0].reshape(-1), 1, rewards, 0.1)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step(graphed, q_in, out)                         # per-device set-up happens in the first call
+    side.synchronize()
+    graphed.q.copy_(_dev(qtab))                          # undo that step's update
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step(graphed, q_in, out)
+        B._check(graphed.lib.mem_retrieve_flags(graphed.h, B._ptr(flags), nq, B._stream()), "mem_retrieve_flags")
+    table = qtab[1].copy()
+    for rep in range(4):
+        queries = _unit(rng, nq, d)
+        q_in.copy_(_dev(queries))
+        graph.replay()
+        torch.cuda.synchronize()
+        e_out = eager.retrieve(_dev(queries), 1, k1, k2, 0.5, want_candidates=True)
+        eager.update_q(e_out[0].reshape(-1), 1, rewards, 0.1)
+        torch.cuda.synchronize()
+        for got, want in zip(out, e_out):
+            assert torch.equal(got.view(torch.int32), want.view(torch.int32)), f"replay {rep}"
+        assert torch.equal(graphed.q.view(torch.int32), eager.q.view(torch.int32)), f"replay {rep}: value table"
+        assert int(flags.abs().sum()) == 0
+        gpu = {"ids": out[0].cpu().numpy(), "scores": out[1].cpu().numpy(), "cand_ids": out[2].cpu().numpy(), "cand_sims": out[3].cpu().numpy()}
+        stats = parity.check_retrieve(orc, orc.round_to_store(rows, DT[dtype]), orc.round_to_store(queries, DT[dtype]), table, k1, k2, 0.5, gpu)
+        assert stats["boundary_swaps"] == 0 and stats["final_swaps"] == 0
+        table, _ = orc.update_q32(table, gpu["ids"].reshape(-1).astype(np.int32), rewards.cpu().numpy(), 0.1)
+        assert np.array_equal(graphed.read_q(1).cpu().numpy().view(np.uint32), table.view(np.uint32)), f"replay {rep}: oracle's table"
+    del graph
+    eager.close()
+    graphed.close()
+
+
 def test_survivor_list_overflow_is_counted(orc):
     """More rows tie with the pool's last member than a survivor list holds (8192): the query is counted by
     mem_counters, the call still returns a valid pool of exact ties, and later calls are unaffected."""
