@@ -96,6 +96,18 @@ __device__ __forceinline__ float lane_select16(const f32x16_t& v, uint64_t lo1, 
     return g0;
 }
 
+// The one non-negative value among the 16 registers of an accumulator block, for lanes that have exactly
+// one: as signed integers, every value with the sign bit set is below every value without it, so the
+// integer maximum of the bit patterns is that value, bit for bit (8 three-operand maxima; no compare
+// masks and no per-lane register choice).
+__device__ __forceinline__ float only_non_negative(const f32x16_t& v) {
+    auto bits = [&](int r) __attribute__((always_inline)) { return (int)__float_as_uint(v[r]); };
+    auto max3 = [](int a, int b, int c) __attribute__((always_inline)) { return max(max(a, b), c); };
+    const int t0 = max3(bits(0), bits(1), bits(2)), t1 = max3(bits(3), bits(4), bits(5)), t2 = max3(bits(6), bits(7), bits(8));
+    const int t3 = max3(bits(9), bits(10), bits(11)), t4 = max3(bits(12), bits(13), bits(14));
+    return __uint_as_float((uint32_t)max(max3(t0, t1, t2), max3(t3, t4, bits(15))));
+}
+
 // Inclusive prefix sum over the 64 lanes of a wavefront (all lanes active): shifts within rows of 16
 // lanes, then the row broadcasts.  Lane 63 ends up with the total.
 __device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t x) {
@@ -175,8 +187,9 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
     float* invq_s = reinterpret_cast<float*>(thp_s + QT);
     uint32_t* cnt_s = reinterpret_cast<uint32_t*>(invq_s + QT);
     uint32_t* base_s = cnt_s + QT;
-    uint64_t* lkey = reinterpret_cast<uint64_t*>(base_s + QT);
-    uint32_t* lq = reinterpret_cast<uint32_t*>(lkey + SCAN_LIST_CAP);
+    constexpr uint32_t LKEY_OFF = 2 * STAGE_BYTES + QT * 16, LQ_OFF = LKEY_OFF + SCAN_LIST_CAP * 8;   // the list's two arrays
+    uint64_t* lkey = reinterpret_cast<uint64_t*>(smem + LKEY_OFF);
+    uint32_t* lq = reinterpret_cast<uint32_t*>(smem + LQ_OFF);
     uint32_t* total_s = lq + SCAN_LIST_CAP;
     uint32_t* allow_s = total_s + 4;                    // masked variant only
     uint32_t* exclude_s = allow_s + QT;
@@ -591,18 +604,43 @@ __global__ __launch_bounds__(64 * WQ * WR) void k_scan_mfma(const void* __restri
                     }
                     ++slot;
                 };
+                // First round, the common case kept free of inner branches: lanes with exactly one survivor in
+                // a block stage it; lanes with more are left to the loop below, and so is everything when the
+                // wavefront's reservation does not fit the list (then no lane needs a room check here).
                 uint32_t rest = 0;
+                const bool fits = (uint32_t)__builtin_amdgcn_readlane((int)wave_base, 63) + (uint32_t)__builtin_amdgcn_readlane((int)incl, 63)
+                                  <= (uint32_t)SCAN_LIST_CAP;                                  // uniform
+                const int ln0 = fresh_lane();
+                const int32_t id0 = (int32_t)(t * TILE_ROWS + wr_u * MR * 32 + (ln0 & 31));   // this lane's row in block b = 0
+                int qla[MQ];                                                                   // this lane's first query in block a
+#pragma unroll
+                for (int a = 0; a < MQ; ++a) qla[a] = (wq_u * MQ + a) * 32 + 4 * (ln0 >> 5);
+                // running LDS addresses of the lane's next list entry (key array, query array)
+                unsigned char* pk = smem + LKEY_OFF + slot * 8u;
+                unsigned char* pq = smem + LQ_OFF + slot * 4u;
 #pragma unroll
                 for (int b = 0; b < MR; ++b)
 #pragma unroll
                     for (int a = 0; a < MQ; ++a) {
                         const uint32_t m = msk[a * MR + b];
-                        const int r = __builtin_ctz(m | 0x10000u);          // 16 for a lane without bits
-                        const float av = pick(a, b, r);
-                        if (m) stage_one(a, b, r, av);
-                        msk[a * MR + b] = m & (m - 1);
-                        rest |= m & (m - 1);
+                        const bool take = fits && __popc(m) == 1;
+                        if (take) {
+                            const int r = __builtin_ctz(m);
+                            const float av = only_non_negative(acc[a][b]);
+                            const int32_t id = id0 + b * 32;
+                            const int ql = qla[a] + r + (r & 12);            // register r holds query 8 * (r >> 2) + (r & 3) of the block
+                            bool ok = true;
+                            if constexpr (MASKED) ok = eligible(mask.tags[id], allow_s[ql], exclude_s[ql]);
+                            *reinterpret_cast<uint64_t*>(pk) = ((uint64_t)__float_as_uint(av) << 32) | (uint32_t)id;
+                            *reinterpret_cast<uint32_t*>(pq) = ok ? (uint32_t)ql : 0xffffu;   // the slot was reserved before the check
+                            pk += 8;
+                            pq += 4;
+                        }
+                        const uint32_t left = take ? 0u : m;
+                        msk[a * MR + b] = left;
+                        rest |= left;
                     }
+                slot = (uint32_t)(pq - (smem + LQ_OFF)) >> 2;
                 if (__builtin_amdgcn_ballot_w64(rest != 0) != 0) {
 #pragma unroll
                     for (int b = 0; b < MR; ++b)
